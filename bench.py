@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused W-way gradient reduction + SGD update on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic gradients:
+one list push of every key (host scheduling, pointer-table lookup, one fused
+kernel launch covering all units), with the updated weights available in place
+(zero-copy pull) and a barrier after the last timed step.  Inputs are resident in
+HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` is aggregated gradient bytes per second
+(N * W * sizeof(grad) / t_step); `roofline` prices the fused kernel's algorithmic
+bytes (N * (W * sizeof(grad) + 16) per launch) against the 8 TB/s HBM peak, with
+the launch duration measured by HIP events on the store's stream;
+`cpu_baseline` is the CPU oracle timed on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+METRIC = "aggregated gradient bytes/s (GB/s, % HBM peak) for W-way reduce+SGD update"
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..5 (3 = ResNet-50-shaped, W=8)")
+    ap.add_argument("--sets", type=int, default=2, help="distinct gradient sets cycled through (fresh buffers each step)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-steps", type=int, default=3)
+    ap.add_argument("--calib-copy", type=int, default=0, metavar="N",
+                    help="also launch the plain copy kernel N times on 1 GiB (byte-counter calibration)")
+    ap.add_argument("--pull-copy", action="store_true", help="also time a copying pull of every key (reported apart)")
+    ap.add_argument("--unroll", type=int, default=0)
+    ap.add_argument("--workgroups-per-cu", type=int, default=-1)
+    ap.add_argument("--nontemporal", type=int, default=-1)
+    ap.add_argument("--xcd-remap", type=int, default=-1)
+    ap.add_argument("--gen-threads", type=int, default=min(16, os.cpu_count() or 1))
+    return ap.parse_args()
+
+
+def read_traffic(workload: str):
+    """HBM bytes per launch from the committed counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    with open(path) as f:
+        for line in f:
+            if ":" in line and not line.lstrip().startswith("#"):
+                k, v = line.split(":", 1)
+                try:
+                    vals[k.strip()] = float(v.split()[0])
+                except (ValueError, IndexError):
+                    pass
+    if "fetch_bytes_per_launch" in vals and "write_bytes_per_launch" in vals:
+        return vals["fetch_bytes_per_launch"] + vals["write_bytes_per_launch"]
+    return None
+
+
+def cpu_baseline(cfg, weights, grads_host, steps: int):
+    """The oracle as it stands: (i) one thread, (ii) the same function on disjoint
+    element ranges from one thread per host core."""
+    from oracle import kv_oracle as orc
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    out = {}
+    for label, threads in (("single", 1), ("all", cores)):
+        st = orc.OracleStore(cfg.numel, cfg.W, lr=cfg.lr, momentum=cfg.momentum, wd=cfg.wd)
+        for k, w in enumerate(weights):
+            st.set_weights(k, w)
+        st.step(grads_host, threads=threads)             # untimed first touch
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            st.step(grads_host, threads=threads)
+        dt = (time.perf_counter() - t0) / steps
+        out[label] = (threads, dt)
+    return out
+
+
+def main() -> int:
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (the W gradient replicas sit in one MI355X's HBM); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import workloads as wl
+    import paper_1802_06949_amd as kv
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    kv.load_library()                                   # fails loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+
+    cfg = wl.get_config(args.config)
+    K = len(cfg.keys)
+    N = cfg.total_numel
+    itemsize = cfg.grad_itemsize
+    tdt = torch.float32 if cfg.grad_dtype == "f32" else torch.float16
+
+    t_gen = time.perf_counter()
+    weights = wl.make_weights(cfg, args.gen_threads)
+    nsets = max(1, args.sets)
+    host_sets = []
+    dev_sets = []
+    for s in range(nsets):
+        g = wl.make_step_gradients(cfg, s, args.gen_threads)
+        dev_sets.append([[torch.from_numpy(a).cuda() for a in gk] for gk in g])
+        if s == 0:
+            host_sets.append(g)
+        del g
+    t_gen = time.perf_counter() - t_gen
+
+    store = kv.KVStore(cfg.numel, cfg.W, cfg.grad_dtype, cfg.bucket_bytes, lr=cfg.lr, momentum=cfg.momentum, wd=cfg.wd,
+                       keep_sum=False, unroll=args.unroll, workgroups_per_cu=args.workgroups_per_cu,
+                       nontemporal=args.nontemporal, xcd_remap=args.xcd_remap)
+    for k, w in enumerate(weights):
+        if w.size:
+            store.set_weights(k, torch.from_numpy(w).cuda())
+    store.wait()
+    keys = list(range(K))
+    lists = [store.make_push_list(keys, d) for d in dev_sets]
+
+    for i in range(args.warmup):
+        store.push_list(lists[i % nsets])
+    store.wait()
+    torch.cuda.synchronize()
+
+    store.timing_begin()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        store.push_list(lists[i % nsets])
+    store.wait()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_ms, launches = store.timing_end()
+
+    t_step = wall / args.steps
+    agg_gbps = N * cfg.W * itemsize / t_step / 1e9
+    alg_bytes_step = cfg.algorithmic_bytes_per_step
+    launches_per_step = launches / args.steps
+    alg_bytes_launch = alg_bytes_step / max(launches_per_step, 1e-9)
+    launch_s = ev_ms * 1e-3 / max(launches, 1)
+    achieved = alg_bytes_launch / launch_s / 1e9
+
+    extra = {}
+    if args.pull_copy:
+        outs = [torch.empty(n, dtype=torch.float32, device="cuda") for n in cfg.numel]
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for k in keys:
+            store.pull(k, outs[k])
+        store.wait()
+        extra["pull_copy_all_keys_ms"] = (time.perf_counter() - t1) * 1e3
+
+    if args.calib_copy > 0:
+        nb = 1 << 30
+        a = torch.empty(nb, dtype=torch.uint8, device="cuda")
+        b = torch.empty(nb, dtype=torch.uint8, device="cuda")
+        for _ in range(args.calib_copy):
+            kv.copy_bytes(b, a, nb)
+        torch.cuda.synchronize()
+        extra["calib_copy_bytes"] = nb
+
+    result = {
+        "metric": METRIC,
+        "value": round(agg_gbps, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(t_step * 1e3, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{cfg.name}: {K} keys, {N} params, W={cfg.W} {cfg.grad_dtype} gradient copies, "
+                        f"bucket {cfg.bucket_bytes} B, lr={cfg.lr} momentum={cfg.momentum} wd={cfg.wd}",
+            "gradient_sets_cycled": nsets,
+            "units": store.plan.num_units,
+            "launches_per_step": launches_per_step,
+            "pull": "zero-copy (weights read in place in the arena)",
+        },
+        "params_per_s": round(N / t_step, 1),
+        "algorithmic_hbm_GBps": round(alg_bytes_step / t_step / 1e9, 2),
+        "algorithmic_hbm_frac_of_peak": round(alg_bytes_step / t_step / 1e9 / HBM_PEAK_GBPS, 4),
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "kv_fused",
+            "achieved": round(achieved, 2),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": read_traffic(cfg.name),
+            "algorithmic_bytes_per_launch": alg_bytes_launch,
+            "avg_launch_us": round(launch_s * 1e6, 3),
+            "launches_timed": launches,
+        },
+    }
+    result.update(extra)
+
+    if not args.no_cpu_baseline:
+        base = cpu_baseline(cfg, weights, host_sets[0], args.cpu_steps)
+        threads, dt = base["all"]
+        result["cpu_baseline"] = {
+            "value": round(N * cfg.W * itemsize / dt / 1e9, 3),
+            "unit": "GB/s",
+            "cores": threads,
+            "kind": "oracle",
+            "sample": f"{args.cpu_steps} full steps of the same workload (all {K} keys), after one untimed step",
+            "ms_per_step": round(dt * 1e3, 2),
+            "single_thread_value": round(N * cfg.W * itemsize / base["single"][1] / 1e9, 3),
+            "single_thread_ms_per_step": round(base["single"][1] * 1e3, 2),
+        }
+    result["input_generation_s"] = round(t_gen, 2)
+    store.close()
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

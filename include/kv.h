@@ -1,0 +1,220 @@
+/*
+ * kv.h - C ABI of the MI355X key-value gradient aggregation library.
+ *
+ * The library implements, on ONE GPU, the push / pull problem of the paper's
+ * "KVStore API" section: every parameter tensor has an integer key; push hands
+ * over the gradient copies of a key, which are aggregated (summed over the W
+ * workers); pull returns the value for the key.  Here the W workers' gradient
+ * copies already sit in this GPU's memory, the aggregate is multiplied by a
+ * scaling factor ("Parallel SGD" section) and the weight update of eq. (1),
+ * extended by momentum and L2 weight decay, is applied in the same kernel:
+ *
+ *     s     = g_0 + g_1 + ... + g_{W-1}          (fp32; order: see kv_sgd_params)
+ *     ghat  = rescale * s
+ *     dw    = momentum * m - lr * (ghat + wd * w)
+ *     w'    = w + dw,   m' = dw                   (eq. (1): w_{t+1} = w_t + dw)
+ *
+ * Every operation is IEEE binary32 with one rounding (no fused multiply-add),
+ * subnormals are kept; half-precision gradients are widened exactly first.
+ *
+ * Scheduling follows the paper's "MPI Dependency Chaining" design: keys smaller
+ * than bucket_bytes are packed into buckets, every bucket or large key is a
+ * "unit", and units are launched strictly in ascending unit index whatever
+ * order the pushes arrive in (the paper orders its collectives with a dummy
+ * write dependency; here the order is a function of the key set alone).
+ *
+ * Conventions
+ *   - All functions return KV_OK (0) or a negative kv_status; none throws or
+ *     aborts.  kv_last_error() gives a message for the last failure.
+ *   - "dev" pointers are device memory of the GPU that was current at kv_init;
+ *     "host" pointers are ordinary host memory.  Nothing passed in is freed by
+ *     the library; everything the library allocates is freed by kv_destroy.
+ *   - A store is not thread-safe: one issuing thread (as in the paper, where
+ *     only the main thread issues engine operations).
+ *   - All device work is issued on the HIP stream given to kv_init.
+ */
+#ifndef KV_H
+#define KV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct kv_store kv_store;   /* opaque, library-owned */
+typedef struct kv_plan  kv_plan;    /* opaque, host-only bucket plan */
+typedef struct kv_chain kv_chain;   /* opaque, host-only launch-order state machine */
+
+enum kv_status {
+    KV_OK             =  0,
+    KV_ERR_ARG        = -1,   /* null pointer, bad count, bad enum value            */
+    KV_ERR_KEY        = -2,   /* key id outside 0..num_keys-1                        */
+    KV_ERR_STATE      = -3,   /* second push of a key before its unit ran; feature off */
+    KV_ERR_ALIGN      = -4,   /* gradient pointer not aligned to its element size    */
+    KV_ERR_INCOMPLETE = -5,   /* wait / barrier while pushed keys cannot be launched  */
+    KV_ERR_HIP        = -6,   /* a HIP runtime call failed (no device, out of memory) */
+    KV_ERR_NOMEM      = -7    /* host allocation failed                              */
+};
+
+enum kv_dtype { KV_F32 = 0, KV_F16 = 1 };                 /* gradient element type   */
+enum kv_reduce_order { KV_REDUCE_SEQUENTIAL = 0,          /* s = g_0; s += g_r, r=1.. */
+                       KV_REDUCE_PAIRWISE   = 1 };        /* balanced tree, see below */
+enum kv_flags { KV_FLAG_KEEP_SUM = 1u };                  /* also store s (kv_pull_grad) */
+
+#define KV_MAX_W 256
+
+/*
+ * Optimizer parameters.  rescale <= 0 selects 1.0f / (float)W, computed once in
+ * fp32 and multiplied.  reduce_order PAIRWISE sums ranks as the tree
+ * sum(lo,1) = g_lo; sum(lo,n) = sum(lo,h) + sum(lo+h, n-h), h the largest
+ * power of two strictly below n.  The first term of SEQUENTIAL is g_0 itself.
+ */
+typedef struct kv_sgd_params {
+    float lr;
+    float momentum;
+    float wd;
+    float rescale;
+    int   reduce_order;
+} kv_sgd_params;
+
+/*
+ * Launch tuning; pass NULL for defaults.  None of these changes any result bit.
+ *   unroll            16-byte vectors per thread per rank in one tile: 1, 2 or 4 (0 = default)
+ *   workgroups_per_cu cap of resident workgroups per compute unit for the grid-stride
+ *                     loop over tiles; 0 = one workgroup per tile
+ *   nontemporal       1 = gradient loads carry the non-temporal hint, 0 = plain, -1 = default
+ *   xcd_remap         1 = tiles are dealt to the 8 XCDs in contiguous ranges, 0 = round robin,
+ *                     -1 = default
+ */
+typedef struct kv_tuning {
+    int unroll;
+    int workgroups_per_cu;
+    int nontemporal;
+    int xcd_remap;
+} kv_tuning;
+
+/* ------------------------------------------------------------------ plan (host only)
+ * The bucket plan is a pure function of (key_numel[], grad_dtype, bucket_bytes);
+ * it needs no GPU.  Policy (the paper has one communication buffer per key and no
+ * buckets; this is this library's extension): scan keys in ascending id; a key's
+ * size is numel * sizeof(grad element) of ONE copy; size >= bucket_bytes makes the
+ * key a unit of its own ("large") and leaves the open bucket open; a smaller key
+ * joins the open bucket if the bucket stays <= bucket_bytes, else closes it and
+ * opens a new one.  Units are numbered by the id of their first key.  In the
+ * weight / momentum arena units lie in index order, keys ascending inside a unit,
+ * every key start rounded up to 16 bytes.
+ */
+int     kv_plan_create(kv_plan** out, int num_keys, const int64_t* key_numel /* host [num_keys], each >= 0 */,
+                       int grad_dtype, size_t bucket_bytes /* >= 1 */);
+void    kv_plan_destroy(kv_plan* plan);
+int     kv_plan_num_keys(const kv_plan* plan);                 /* < 0 on NULL */
+int     kv_plan_num_units(const kv_plan* plan);
+/* Unit description.  keys_out (host, may be NULL) receives at most cap key ids in
+ * ascending order; *nkeys_out the full count; *is_large_out 1 for a large-key unit. */
+int     kv_plan_unit(const kv_plan* plan, int unit, int* is_large_out, int* nkeys_out, int* keys_out, int cap);
+/* Unit and arena element offset of a key. */
+int     kv_plan_key(const kv_plan* plan, int key, int* unit_out, int64_t* arena_offset_out);
+int64_t kv_plan_arena_numel(const kv_plan* plan);              /* fp32 elements incl. padding */
+
+/* ------------------------------------------------------------------ chain (host only)
+ * The launch-order state machine the store runs on every push, exposed so that the
+ * ordering invariant can be checked without a GPU.  kv_chain_mark records the push
+ * of one key (KV_ERR_STATE if the key is already marked and its unit has not run);
+ * kv_chain_next_run then yields, repeatedly, maximal runs [first, first + n) of
+ * consecutive ready units in ascending index, wrapping to unit 0 for the next
+ * iteration; it returns 1 while it yields a run and 0 when nothing is ready.
+ * A unit is ready when all its keys are marked; a ready unit still waits for every
+ * lower unit of the same iteration (the paper's chain of write dependencies).
+ */
+int     kv_chain_create(kv_chain** out, const kv_plan* plan /* must outlive the chain */);
+void    kv_chain_destroy(kv_chain* chain);
+int     kv_chain_mark(kv_chain* chain, int key);
+int     kv_chain_next_run(kv_chain* chain, int* first_unit_out, int* n_units_out);
+int     kv_chain_pending_keys(const kv_chain* chain);          /* marked, unit not yet run */
+int     kv_chain_next_unit(const kv_chain* chain);             /* 0 when an iteration is complete */
+
+/* ------------------------------------------------------------------ store
+ * kv_init: KVStore.init for all keys at once (keys are 0..num_keys-1 in the linear
+ * order of the tensors, as the paper assigns them).  Builds the plan, allocates the
+ * fp32 weight and momentum arenas (zero-filled) on the current device and uploads
+ * the tile tables.  hip_stream is a hipStream_t (NULL = the default stream) that
+ * must outlive the store.  W in 1..KV_MAX_W.  flags: kv_flags.  tuning may be NULL.
+ */
+int kv_init(kv_store** out, int num_keys, const int64_t* key_numel /* host */, int grad_dtype, int W,
+            size_t bucket_bytes, const kv_sgd_params* params /* host */, unsigned flags,
+            const kv_tuning* tuning /* host or NULL */, void* hip_stream);
+void kv_destroy(kv_store* store);                              /* drains the stream first; NULL is a no-op */
+
+/* Initial value of a key (the paper broadcasts rank 0's value; here there is one
+ * copy) and momentum restore.  src: numel fp32 values, device or host memory;
+ * copied on the store's stream, in order with pushes and pulls. */
+int kv_set_weights (kv_store* store, int key, const void* src_f32);
+int kv_set_momentum(kv_store* store, int key, const void* src_f32);
+int kv_set_lr(kv_store* store, float lr);                      /* takes effect at the next launch */
+
+/*
+ * kv_push: hands over the W gradient copies of one key (KVStore push; it
+ * "aggregates all the gradients of the same key").  dev_grads: host array of W
+ * device pointers, each to numel elements of the gradient dtype, aligned at least
+ * to the element size (16-byte alignment of all W selects the 128-bit path).
+ * The gradients are read in place, asynchronously: they must stay valid and
+ * unmodified until kv_wait returns or the stream is synchronised.  Never blocks.
+ * When the push completes the next unit in order, that unit and every directly
+ * following ready unit are launched as ONE kernel launch.
+ */
+int kv_push(kv_store* store, int key, const void* const* dev_grads /* host [W] */);
+/* List form (the paper's push takes lists of keys and tensors): marks all keys
+ * first, then launches; pushing all keys gives one launch per iteration.
+ * dev_grads is a host array [nkeys * W], key-major.  Either every key of the list
+ * is accepted or none is. */
+int kv_push_list(kv_store* store, int nkeys, const int* keys /* host */, const void* const* dev_grads /* host */);
+
+/*
+ * kv_pull: copies the key's current weights (numel fp32) to dev_out on the store's
+ * stream; after a push of the same key it observes the updated value (if the key's
+ * unit has not been launched yet the copy is queued and issued right after that
+ * launch).  kv_pull_grad copies the raw fp32 sum s of the last step (the value the
+ * paper's pull returns); it needs KV_FLAG_KEEP_SUM, else KV_ERR_STATE.
+ */
+int kv_pull(kv_store* store, int key, void* dev_out_f32);
+int kv_pull_grad(kv_store* store, int key, void* dev_out_f32);
+int kv_pull_momentum(kv_store* store, int key, void* dev_out_f32);
+/* Zero-copy pull: device address of the key's weights inside the arena (numel fp32,
+ * 16-byte aligned, valid until kv_destroy; contents change with every step). */
+int kv_weights_ptr(kv_store* store, int key, void** dev_ptr_out);
+
+/*
+ * kv_wait(key >= 0): blocks the host until the key's last launched update (and all
+ * earlier work on the stream) is complete; KV_ERR_INCOMPLETE, without blocking, if
+ * the key is pushed but its unit cannot be launched yet.
+ * kv_wait(-1): barrier (the paper's Kvstore.barrier): drains the stream, then
+ * returns KV_ERR_INCOMPLETE if an iteration is only partly pushed or launched.
+ */
+int kv_wait(kv_store* store, int key);
+
+/* ------------------------------------------------------------------ introspection
+ * The plan in use (owned by the store). */
+const kv_plan* kv_store_plan(const kv_store* store);
+/* Launch log: total number of kernel launches so far in *total_out; the most
+ * recent min(total, cap) launches, oldest first, as (first_unit, n_units) pairs. */
+int kv_launch_log(const kv_store* store, int64_t* total_out, int* first_unit_out, int* n_units_out, int cap);
+/* GPU time between two points of the store's stream, measured with HIP events:
+ * begin records an event; end records another, waits for it and returns the
+ * elapsed milliseconds and the number of kernel launches issued in between. */
+int kv_timing_begin(kv_store* store);
+int kv_timing_end(kv_store* store, float* ms_out, int64_t* launches_out);
+/* Plain streaming copy kernel (float4 grid-stride) of `bytes` bytes (multiple of 16,
+ * both pointers 16-byte aligned) on hip_stream: the known-size kernel against which
+ * hardware byte counters are calibrated. */
+int kv_copy_bytes(void* dev_dst, const void* dev_src, size_t bytes, void* hip_stream);
+
+/* Message for the last failure on this store (or, with NULL, of the last failed
+ * kv_init / kv_plan_create / kv_chain_create on this thread).  Never NULL. */
+const char* kv_last_error(const kv_store* store);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KV_H */

@@ -1,0 +1,47 @@
+// Structures shared by the host scheduler and the kernels.
+#pragma once
+#include <stdint.h>
+
+constexpr int KV_THREADS = 256;          // 4 wavefronts of 64 lanes per workgroup
+
+// One tile: a contiguous piece of one key handled by one workgroup pass.
+// Element counts; seg_off is a multiple of the tile size, so 16-byte vectors of
+// the arena and of 16-byte-aligned gradient buffers line up.
+struct alignas(16) KvTile {
+    int32_t seg;       // segment (key) index in launch order
+    int32_t count;     // elements in this tile (<= tile size; the last tile of a key may be ragged)
+    int64_t seg_off;   // first element of the tile inside the key
+};
+
+// One segment = one key as laid out in the arenas.
+struct alignas(16) KvSeg {
+    int64_t arena_off; // first element of the key in the w / m / s arenas (multiple of 4)
+    int64_t numel;
+};
+
+struct KvLaunchArgs {
+    const KvTile* tiles;          // device, all tiles of the store in (unit, key, offset) order
+    const KvSeg* segs;            // device, all segments in (unit, key) order
+    const void* const* gptrs;     // device, [num_segs * W] gradient pointers, segment-major
+    float* w;                     // weight arena
+    float* m;                     // momentum arena
+    float* s;                     // raw-sum arena (only read by kernels built with KEEP)
+    int64_t tile_lo;              // first tile of this launch
+    int64_t tile_hi;              // one past the last tile
+    int32_t W;
+    int32_t xcd_remap;
+    float lr, momentum, wd, rescale;
+};
+
+// Launch selector: every field picks a template instantiation or a launch shape.
+struct KvKernelSel {
+    int grad_f16;      // 0: fp32 gradients, 1: fp16
+    int W;
+    int pairwise;      // 0: rank-order left fold, 1: balanced tree
+    int keep_sum;
+    int unroll;        // 1, 2, 4
+    int nontemporal;
+};
+
+// Elements per tile for a gradient dtype and unroll factor.
+constexpr int kv_tile_elems(int grad_f16, int unroll) { return KV_THREADS * (grad_f16 ? 8 : 4) * unroll; }

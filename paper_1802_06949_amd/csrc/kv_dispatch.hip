@@ -1,0 +1,36 @@
+// Kernel selection and the plain copy kernel.
+#include <hip/hip_runtime.h>
+
+#include "kv_kernels.hpp"
+
+hipError_t kv_launch_fused(const KvKernelSel& sel, const KvLaunchArgs& args, unsigned grid, hipStream_t stream) {
+    if (args.tile_hi <= args.tile_lo || grid == 0) return hipSuccess;
+#define KV_CASE(W) \
+    case W: return sel.grad_f16 ? kv_launch_fused_f1_w##W(sel, args, grid, stream) \
+                                : kv_launch_fused_f0_w##W(sel, args, grid, stream);
+    switch (sel.W) {
+        KV_CASE(2) KV_CASE(4) KV_CASE(8) KV_CASE(16) KV_CASE(32)
+        default: break;
+    }
+#undef KV_CASE
+    return sel.grad_f16 ? kv_launch_fused_f1_w0(sel, args, grid, stream) : kv_launch_fused_f0_w0(sel, args, grid, stream);
+}
+
+namespace {
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__global__ void __launch_bounds__(KV_THREADS) kv_copy_kernel(f32x4* __restrict__ dst, const f32x4* __restrict__ src, size_t nvec) {
+    const size_t stride = (size_t)gridDim.x * KV_THREADS;
+    for (size_t i = (size_t)blockIdx.x * KV_THREADS + threadIdx.x; i < nvec; i += stride) dst[i] = src[i];
+}
+}  // namespace
+
+hipError_t kv_launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream) {
+    const size_t nvec = bytes / 16;
+    if (nvec == 0) return hipSuccess;
+    size_t blocks = (nvec + KV_THREADS - 1) / KV_THREADS;
+    if (blocks > 256u * 16u) blocks = 256u * 16u;
+    hipLaunchKernelGGL(kv_copy_kernel, dim3((unsigned)blocks), dim3(KV_THREADS), 0, stream,
+                       static_cast<f32x4*>(dst), static_cast<const f32x4*>(src), nvec);
+    return hipGetLastError();
+}

@@ -1,0 +1,355 @@
+// Fused W-way gradient reduction + scale + momentum-SGD update for gfx950.
+//
+// This translation unit is compiled once per (gradient dtype, W) pair, selected
+// by -DKV_TU_F16={0,1} and -DKV_TU_W={0,2,4,8,16,32} (0 = W known only at run
+// time), and exports one launcher, kv_launch_fused_f<F16>_w<W>.
+//
+// The path is a pure streaming pass: per parameter element it reads W gradient
+// values once, reads w and m, and writes w' and m'.  There is no reuse, so there
+// is no LDS staging and no MFMA; what matters is that every lane issues
+// independent 128-bit loads (all W ranks, and `U` vectors per rank, are in flight
+// before the first add) and that a wavefront's 64 lanes cover 1 KiB of contiguous
+// memory per load instruction.
+//
+// Arithmetic contract (must match bit for bit what the header of the C ABI
+// states): each element is owned by one lane for all W ranks, the ranks are
+// folded in a fixed order, every operation is a separate IEEE binary32 operation.
+// The file must be compiled with -ffp-contract=off.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kv_device.hpp"
+#include "kv_kernels.hpp"
+
+#ifndef KV_TU_F16
+#error "KV_TU_F16 must be defined"
+#endif
+#ifndef KV_TU_W
+#error "KV_TU_W must be defined"
+#endif
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+template <bool F16> struct Grad;
+template <> struct Grad<false> {
+    using elem = float;
+    using vec = f32x4;
+    static constexpr int VEC = 4;
+    static __device__ __forceinline__ void widen(const vec& v, float (&o)[4]) {
+        o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+    }
+    static __device__ __forceinline__ float widen1(elem e) { return e; }
+};
+template <> struct Grad<true> {
+    using elem = _Float16;
+    using vec = f16x8;
+    static constexpr int VEC = 8;
+    static __device__ __forceinline__ void widen(const vec& v, float (&o)[8]) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = (float)v[i];      // exact: every binary16 value is a binary32 value
+    }
+    static __device__ __forceinline__ float widen1(elem e) { return (float)e; }
+};
+
+template <bool NT, typename T>
+__device__ __forceinline__ T load_grad(const T* p) {
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+// Rank-order left fold: s = g_0; s = s + g_r.  The first term is taken as is.
+template <int NV> struct FoldSeq {
+    float acc[NV];
+    unsigned count = 0;
+    __device__ __forceinline__ void push(const float (&v)[NV]) {
+        if (count == 0) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) acc[i] = v[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) acc[i] = acc[i] + v[i];
+        }
+        ++count;
+    }
+    __device__ __forceinline__ void finish(float (&o)[NV]) const {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) o[i] = acc[i];
+    }
+};
+
+// Balanced tree in rank order, evaluated as a stream with a binary-counter stack:
+// level l holds the sum of a complete block of 2^l consecutive ranks.  After n
+// pushes the occupied levels are the set bits of n, leftmost block highest; the
+// final merge runs from the lowest level up with the earlier block on the left.
+// This is sum(lo,n) = sum(lo,h) + sum(lo+h,n-h), h = largest power of two < n.
+template <int NV> struct FoldPair {
+    static constexpr int L = 9;               // up to 2^8 = KV_MAX_W ranks
+    float st[L][NV];
+    unsigned count = 0;
+    __device__ __forceinline__ void push(const float (&v)[NV]) {
+        float cur[NV];
+#pragma unroll
+        for (int i = 0; i < NV; ++i) cur[i] = v[i];
+        unsigned c = count;
+        bool placed = false;
+#pragma unroll
+        for (int l = 0; l < L; ++l) {
+            if (!placed) {
+                if (c & 1u) {
+#pragma unroll
+                    for (int i = 0; i < NV; ++i) cur[i] = st[l][i] + cur[i];
+                    c >>= 1;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < NV; ++i) st[l][i] = cur[i];
+                    placed = true;
+                }
+            }
+        }
+        ++count;
+    }
+    __device__ __forceinline__ void finish(float (&o)[NV]) const {
+        bool have = false;
+#pragma unroll
+        for (int l = 0; l < L; ++l) {
+            if ((count >> l) & 1u) {
+                if (!have) {
+#pragma unroll
+                    for (int i = 0; i < NV; ++i) o[i] = st[l][i];
+                    have = true;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < NV; ++i) o[i] = st[l][i] + o[i];
+                }
+            }
+        }
+    }
+};
+
+template <int NV, bool PAIRWISE> struct FoldSel { using type = FoldSeq<NV>; };
+template <int NV> struct FoldSel<NV, true> { using type = FoldPair<NV>; };
+
+// Sum over ranks of the 16-byte vector that starts at element `eoff` of the key.
+template <bool F16, int WT, bool PAIRWISE, bool NT>
+__device__ __forceinline__ void reduce_vec(const typename Grad<F16>::elem* const* __restrict__ gp, int W,
+                                           int64_t eoff, float (&s)[Grad<F16>::VEC]) {
+    using G = Grad<F16>;
+    using V = typename G::vec;
+    constexpr int NV = G::VEC;
+    typename FoldSel<NV, PAIRWISE>::type f;
+    if constexpr (WT > 0) {
+        constexpr int CH = WT > 16 ? 16 : WT;      // ranks whose loads are issued back to back
+#pragma unroll
+        for (int r0 = 0; r0 < WT; r0 += CH) {
+            V g[CH];
+#pragma unroll
+            for (int j = 0; j < CH; ++j) g[j] = load_grad<NT>(reinterpret_cast<const V*>(gp[r0 + j] + eoff));
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                float t[NV];
+                G::widen(g[j], t);
+                f.push(t);
+            }
+        }
+    } else {
+        for (int r0 = 0; r0 < W; r0 += 4) {
+            V g[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (r0 + j < W) g[j] = load_grad<NT>(reinterpret_cast<const V*>(gp[r0 + j] + eoff));
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (r0 + j < W) {
+                    float t[NV];
+                    G::widen(g[j], t);
+                    f.push(t);
+                }
+            }
+        }
+    }
+    f.finish(s);
+}
+
+// Same for a single element (ragged tails and gradient buffers that are not
+// 16-byte aligned).
+template <bool F16, int WT, bool PAIRWISE>
+__device__ __forceinline__ float reduce_one(const typename Grad<F16>::elem* const* __restrict__ gp, int W, int64_t e) {
+    using G = Grad<F16>;
+    typename FoldSel<1, PAIRWISE>::type f;
+    const int n = WT > 0 ? WT : W;
+    for (int r = 0; r < n; ++r) {
+        float t[1] = {G::widen1(gp[r][e])};
+        f.push(t);
+    }
+    float o[1];
+    f.finish(o);
+    return o[0];
+}
+
+// eq. (1) extended by momentum and weight decay; one rounding per operation.
+__device__ __forceinline__ void sgd_update(float s, float w, float m, float rescale, float lr, float mu, float wd,
+                                           float& w_new, float& m_new) {
+    const float ghat = rescale * s;
+    const float wdw = wd * w;
+    const float t = ghat + wdw;
+    const float mm = mu * m;
+    const float lt = lr * t;
+    const float dw = mm - lt;
+    m_new = dw;
+    w_new = w + dw;
+}
+
+template <bool F16, int WT, bool PAIRWISE, bool KEEP>
+__device__ __forceinline__ void scalar_element(const typename Grad<F16>::elem* const* __restrict__ gp, int W, int64_t e,
+                                               float* __restrict__ wp, float* __restrict__ mp, float* __restrict__ sp,
+                                               const KvLaunchArgs& a) {
+    const float s = reduce_one<F16, WT, PAIRWISE>(gp, W, e);
+    float wn, mn;
+    sgd_update(s, wp[e], mp[e], a.rescale, a.lr, a.momentum, a.wd, wn, mn);
+    if constexpr (KEEP) sp[e] = s;
+    mp[e] = mn;
+    wp[e] = wn;
+}
+
+template <bool F16, int WT, bool PAIRWISE, bool KEEP, int U, bool NT>
+__global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
+    using G = Grad<F16>;
+    using E = typename G::elem;
+    constexpr int NV = G::VEC;
+    constexpr int Q = NV / 4;                           // float4 pieces of w / m per gradient vector
+    constexpr int TILE = KV_THREADS * NV * U;
+    const int W = WT > 0 ? WT : a.W;
+    const int tid = threadIdx.x;
+
+    const int64_t ntiles = a.tile_hi - a.tile_lo;
+    // With xcd_remap, consecutive workgroup ids (which the hardware deals round-robin
+    // to the 8 XCDs) are sent to 8 contiguous tile ranges, one per XCD.
+    const int64_t chunk = (ntiles + 7) >> 3;
+    const int64_t span = a.xcd_remap ? chunk * 8 : ntiles;
+
+    for (int64_t i = blockIdx.x; i < span; i += gridDim.x) {
+        int64_t t = i;
+        if (a.xcd_remap) {
+            t = (i & 7) * chunk + (i >> 3);
+            if (t >= ntiles) continue;
+        }
+        const KvTile td = a.tiles[a.tile_lo + t];
+        const KvSeg sd = a.segs[td.seg];
+        const E* const* __restrict__ gp = reinterpret_cast<const E* const*>(a.gptrs) + (int64_t)td.seg * W;
+
+        uintptr_t bits = 0;
+        for (int r = 0; r < W; ++r) bits |= reinterpret_cast<uintptr_t>(gp[r]);
+        const bool vec_ok = (bits & 15u) == 0;
+
+        const int64_t e0 = td.seg_off;
+        float* __restrict__ wp = a.w + sd.arena_off;
+        float* __restrict__ mp = a.m + sd.arena_off;
+        float* __restrict__ sp = KEEP ? a.s + sd.arena_off : nullptr;
+
+        if (vec_ok && td.count == TILE) {
+            // full tile: issue every load of every unrolled vector before the first store
+            f32x4 w4[U][Q], m4[U][Q];
+            float s[U][NV];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t e = e0 + (int64_t)(tid + u * KV_THREADS) * NV;
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    w4[u][q] = *reinterpret_cast<const f32x4*>(wp + e + 4 * q);
+                    m4[u][q] = *reinterpret_cast<const f32x4*>(mp + e + 4 * q);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t e = e0 + (int64_t)(tid + u * KV_THREADS) * NV;
+                reduce_vec<F16, WT, PAIRWISE, NT>(gp, W, e, s[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t e = e0 + (int64_t)(tid + u * KV_THREADS) * NV;
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    f32x4 wn, mn, sv;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        float wo, mo;
+                        sgd_update(s[u][4 * q + c], w4[u][q][c], m4[u][q][c], a.rescale, a.lr, a.momentum, a.wd, wo, mo);
+                        wn[c] = wo; mn[c] = mo; sv[c] = s[u][4 * q + c];
+                    }
+                    if constexpr (KEEP) *reinterpret_cast<f32x4*>(sp + e + 4 * q) = sv;
+                    *reinterpret_cast<f32x4*>(mp + e + 4 * q) = mn;
+                    *reinterpret_cast<f32x4*>(wp + e + 4 * q) = wn;
+                }
+            }
+        } else if (vec_ok) {
+            // ragged tile: whole vectors first, then at most NV-1 single elements
+            const int nvec = td.count / NV;
+            for (int v = tid; v < nvec; v += KV_THREADS) {
+                const int64_t e = e0 + (int64_t)v * NV;
+                float s[NV];
+                reduce_vec<F16, WT, PAIRWISE, NT>(gp, W, e, s);
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    const f32x4 wv = *reinterpret_cast<const f32x4*>(wp + e + 4 * q);
+                    const f32x4 mv = *reinterpret_cast<const f32x4*>(mp + e + 4 * q);
+                    f32x4 wn, mn, sv;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        float wo, mo;
+                        sgd_update(s[4 * q + c], wv[c], mv[c], a.rescale, a.lr, a.momentum, a.wd, wo, mo);
+                        wn[c] = wo; mn[c] = mo; sv[c] = s[4 * q + c];
+                    }
+                    if constexpr (KEEP) *reinterpret_cast<f32x4*>(sp + e + 4 * q) = sv;
+                    *reinterpret_cast<f32x4*>(mp + e + 4 * q) = mn;
+                    *reinterpret_cast<f32x4*>(wp + e + 4 * q) = wn;
+                }
+            }
+            const int rem = td.count - nvec * NV;
+            if (tid < rem) scalar_element<F16, WT, PAIRWISE, KEEP>(gp, W, e0 + (int64_t)nvec * NV + tid, wp, mp, sp, a);
+        } else {
+            for (int k = tid; k < td.count; k += KV_THREADS)
+                scalar_element<F16, WT, PAIRWISE, KEEP>(gp, W, e0 + k, wp, mp, sp, a);
+        }
+    }
+}
+
+template <bool F16, int WT, bool PAIRWISE, bool KEEP, int U, bool NT>
+hipError_t launch_one(const KvLaunchArgs& a, unsigned grid, hipStream_t st) {
+    hipLaunchKernelGGL((kv_fused<F16, WT, PAIRWISE, KEEP, U, NT>), dim3(grid), dim3(KV_THREADS), 0, st, a);
+    return hipGetLastError();
+}
+
+template <bool F16, int WT, bool PAIRWISE, bool KEEP, int U>
+hipError_t pick_nt(const KvKernelSel& s, const KvLaunchArgs& a, unsigned grid, hipStream_t st) {
+    return s.nontemporal ? launch_one<F16, WT, PAIRWISE, KEEP, U, true>(a, grid, st)
+                         : launch_one<F16, WT, PAIRWISE, KEEP, U, false>(a, grid, st);
+}
+
+template <bool F16, int WT, bool PAIRWISE, bool KEEP>
+hipError_t pick_u(const KvKernelSel& s, const KvLaunchArgs& a, unsigned grid, hipStream_t st) {
+    switch (s.unroll) {
+        case 1: return pick_nt<F16, WT, PAIRWISE, KEEP, 1>(s, a, grid, st);
+        case 2: return pick_nt<F16, WT, PAIRWISE, KEEP, 2>(s, a, grid, st);
+        case 4: return pick_nt<F16, WT, PAIRWISE, KEEP, 4>(s, a, grid, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <bool F16, int WT>
+hipError_t pick_order_keep(const KvKernelSel& s, const KvLaunchArgs& a, unsigned grid, hipStream_t st) {
+    if (s.pairwise) return s.keep_sum ? pick_u<F16, WT, true, true>(s, a, grid, st) : pick_u<F16, WT, true, false>(s, a, grid, st);
+    return s.keep_sum ? pick_u<F16, WT, false, true>(s, a, grid, st) : pick_u<F16, WT, false, false>(s, a, grid, st);
+}
+
+}  // namespace
+
+#define KV_CAT2(a, b, c, d) a##b##c##d
+#define KV_CAT(a, b, c, d) KV_CAT2(a, b, c, d)
+
+hipError_t KV_CAT(kv_launch_fused_f, KV_TU_F16, _w, KV_TU_W)(const KvKernelSel& sel, const KvLaunchArgs& args,
+                                                             unsigned grid, hipStream_t stream) {
+    return pick_order_keep<(KV_TU_F16 != 0), KV_TU_W>(sel, args, grid, stream);
+}

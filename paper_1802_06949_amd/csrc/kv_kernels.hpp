@@ -1,0 +1,20 @@
+// Host-callable launchers of the HIP kernels.
+#pragma once
+#include <hip/hip_runtime_api.h>
+#include <stddef.h>
+
+#include "kv_device.hpp"
+
+// One launcher per (gradient dtype, W) translation unit of kv_fused.hip.
+#define KV_DECL_FUSED(F, W) \
+    hipError_t kv_launch_fused_f##F##_w##W(const KvKernelSel&, const KvLaunchArgs&, unsigned grid, hipStream_t);
+KV_DECL_FUSED(0, 0) KV_DECL_FUSED(0, 2) KV_DECL_FUSED(0, 4) KV_DECL_FUSED(0, 8) KV_DECL_FUSED(0, 16) KV_DECL_FUSED(0, 32)
+KV_DECL_FUSED(1, 0) KV_DECL_FUSED(1, 2) KV_DECL_FUSED(1, 4) KV_DECL_FUSED(1, 8) KV_DECL_FUSED(1, 16) KV_DECL_FUSED(1, 32)
+#undef KV_DECL_FUSED
+
+// Picks the instantiation for sel (a W without a dedicated build uses the
+// run-time-W kernel) and launches it over tiles [args.tile_lo, args.tile_hi).
+hipError_t kv_launch_fused(const KvKernelSel& sel, const KvLaunchArgs& args, unsigned grid, hipStream_t stream);
+
+// Plain float4 grid-stride copy of `bytes` bytes (multiple of 16).
+hipError_t kv_launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);

@@ -1,0 +1,654 @@
+// C ABI of the key-value gradient aggregation store (see include/kv.h).
+//
+// Host side of the hot path: records the gradient pointers of every pushed key,
+// runs the in-order launch chain and issues ONE fused kernel launch per maximal
+// run of consecutive ready units.  The gradient pointers reach the kernel through
+// a small device table; tables are cached so that a training loop that reuses its
+// gradient buffers (or alternates between a few sets) uploads nothing in steady
+// state.
+#include <hip/hip_runtime_api.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "../../include/kv.h"
+#include "kv_kernels.hpp"
+#include "kv_plan.hpp"
+
+namespace {
+
+thread_local std::string g_err = "";
+
+void set_err(std::string& dst, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    dst = buf;
+}
+
+constexpr int NSLOT = 4;    // cached device pointer tables
+constexpr int NSTAGE = 8;   // pinned staging chunks in flight
+constexpr int LOG_CAP = 4096;
+
+struct Deferred {
+    int key;
+    void* dst;
+    int what;               // 0 = weights, 1 = momentum, 2 = raw sum
+};
+
+}  // namespace
+
+struct kv_store {
+    kv_plan plan;
+    kv_chain chain;
+    int W = 0;
+    unsigned flags = 0;
+    kv_sgd_params p{};
+    float rescale = 1.0f;
+    int unroll = 2, wg_per_cu = 0, nontemporal = 1, xcd_remap = 0;
+    int tile_elems = 0;
+    hipStream_t stream = nullptr;
+    int device = 0;
+    int num_cus = 256;
+
+    float* w = nullptr;
+    float* m = nullptr;
+    float* s = nullptr;
+    KvTile* d_tiles = nullptr;
+    KvSeg* d_segs = nullptr;
+    std::vector<int64_t> unit_tile_begin;
+
+    size_t table_elems = 0;                       // num_segs * W
+    std::vector<const void*> cur_ptrs;            // host: pointers of the pushes not yet launched
+    const void** d_slot[NSLOT] = {nullptr, nullptr, nullptr, nullptr};
+    std::vector<const void*> mirror[NSLOT];       // host copy of what each device table holds
+    std::vector<uint8_t> row_valid[NSLOT];        // per segment
+    int last_slot = 0;
+    int next_victim = 0;
+
+    const void** h_stage = nullptr;               // pinned, NSTAGE * table_elems
+    hipEvent_t stage_ev[NSTAGE] = {};
+    bool stage_busy[NSTAGE] = {};
+    int stage_next = 0;
+
+    std::vector<std::vector<Deferred>> deferred;  // per unit
+
+    std::vector<std::pair<int, int>> log;
+    int64_t launches_total = 0;
+
+    hipEvent_t t0 = nullptr, t1 = nullptr;
+    int64_t launches_at_begin = 0;
+    bool timing_active = false;
+
+    std::string err;
+};
+
+namespace {
+
+#define KV_HIP(store, call)                                                                   \
+    do {                                                                                      \
+        hipError_t e_ = (call);                                                               \
+        if (e_ != hipSuccess) {                                                               \
+            set_err((store)->err, "%s failed: %s", #call, hipGetErrorString(e_));             \
+            return KV_ERR_HIP;                                                                \
+        }                                                                                     \
+    } while (0)
+
+void free_store(kv_store* st) {
+    if (!st) return;
+    if (st->w) (void)hipFree(st->w);
+    if (st->m) (void)hipFree(st->m);
+    if (st->s) (void)hipFree(st->s);
+    if (st->d_tiles) (void)hipFree(st->d_tiles);
+    if (st->d_segs) (void)hipFree(st->d_segs);
+    for (int i = 0; i < NSLOT; ++i)
+        if (st->d_slot[i]) (void)hipFree(st->d_slot[i]);
+    if (st->h_stage) (void)hipHostFree(st->h_stage);
+    for (int i = 0; i < NSTAGE; ++i)
+        if (st->stage_ev[i]) (void)hipEventDestroy(st->stage_ev[i]);
+    if (st->t0) (void)hipEventDestroy(st->t0);
+    if (st->t1) (void)hipEventDestroy(st->t1);
+    delete st;
+}
+
+int check_key(kv_store* st, int key) {
+    if (key < 0 || key >= st->plan.num_keys) {
+        set_err(st->err, "key %d outside 0..%d", key, st->plan.num_keys - 1);
+        return KV_ERR_KEY;
+    }
+    return KV_OK;
+}
+
+// Device table that holds the current pointers of segments [s0, s1); uploads them if
+// no cached table matches.
+int table_for(kv_store* st, int s0, int s1, const void* const** table_out) {
+    const size_t W = (size_t)st->W;
+    const size_t lo = (size_t)s0 * W, n = (size_t)(s1 - s0) * W;
+    for (int k = 0; k < NSLOT; ++k) {
+        const int slot = (st->last_slot + k) % NSLOT;
+        bool valid = true;
+        for (int sgm = s0; sgm < s1 && valid; ++sgm) valid = st->row_valid[slot][sgm] != 0;
+        if (valid && std::memcmp(&st->mirror[slot][lo], &st->cur_ptrs[lo], n * sizeof(void*)) == 0) {
+            st->last_slot = slot;
+            *table_out = st->d_slot[slot];
+            return KV_OK;
+        }
+    }
+    // Prefer the table used last if these rows are still free in it (keeps the rows of
+    // one iteration together); else evict round robin.
+    int slot = st->last_slot;
+    bool free_rows = true;
+    for (int sgm = s0; sgm < s1 && free_rows; ++sgm) free_rows = st->row_valid[slot][sgm] == 0;
+    if (!free_rows) {
+        slot = st->next_victim;
+        if (slot == st->last_slot) slot = (slot + 1) % NSLOT;
+        st->next_victim = (slot + 1) % NSLOT;
+    }
+    const int chunk = st->stage_next;
+    st->stage_next = (st->stage_next + 1) % NSTAGE;
+    if (st->stage_busy[chunk]) {
+        KV_HIP(st, hipEventSynchronize(st->stage_ev[chunk]));
+        st->stage_busy[chunk] = false;
+    }
+    const void** stage = st->h_stage + (size_t)chunk * st->table_elems + lo;
+    std::memcpy(stage, &st->cur_ptrs[lo], n * sizeof(void*));
+    KV_HIP(st, hipMemcpyAsync(st->d_slot[slot] + lo, stage, n * sizeof(void*), hipMemcpyHostToDevice, st->stream));
+    KV_HIP(st, hipEventRecord(st->stage_ev[chunk], st->stream));
+    st->stage_busy[chunk] = true;
+    std::memcpy(&st->mirror[slot][lo], &st->cur_ptrs[lo], n * sizeof(void*));
+    for (int sgm = s0; sgm < s1; ++sgm) st->row_valid[slot][sgm] = 1;
+    st->last_slot = slot;
+    *table_out = st->d_slot[slot];
+    return KV_OK;
+}
+
+int issue_copy_out(kv_store* st, int key, void* dst, int what) {
+    const float* base = what == 0 ? st->w : what == 1 ? st->m : st->s;
+    const int64_t n = st->plan.numel[key];
+    if (n == 0) return KV_OK;
+    KV_HIP(st, hipMemcpyAsync(dst, base + st->plan.key_arena_off[key], (size_t)n * sizeof(float), hipMemcpyDefault,
+                              st->stream));
+    return KV_OK;
+}
+
+// Launches units [first, first + n) as one kernel, then the pulls queued on them.
+int launch_run(kv_store* st, int first, int n) {
+    const int s0 = st->plan.units[first].seg_begin;
+    const int s1 = st->plan.units[first + n - 1].seg_end;
+    const int64_t tile_lo = st->unit_tile_begin[first];
+    const int64_t tile_hi = st->unit_tile_begin[first + n];
+    if (tile_hi > tile_lo) {
+        const void* const* table = nullptr;
+        int rc = table_for(st, s0, s1, &table);
+        if (rc != KV_OK) return rc;
+        KvLaunchArgs a{};
+        a.tiles = st->d_tiles;
+        a.segs = st->d_segs;
+        a.gptrs = table;
+        a.w = st->w;
+        a.m = st->m;
+        a.s = st->s;
+        a.tile_lo = tile_lo;
+        a.tile_hi = tile_hi;
+        a.W = st->W;
+        a.xcd_remap = st->xcd_remap;
+        a.lr = st->p.lr;
+        a.momentum = st->p.momentum;
+        a.wd = st->p.wd;
+        a.rescale = st->rescale;
+        KvKernelSel sel{};
+        sel.grad_f16 = st->plan.grad_dtype == KV_F16;
+        sel.W = st->W;
+        sel.pairwise = st->p.reduce_order == KV_REDUCE_PAIRWISE;
+        sel.keep_sum = (st->flags & KV_FLAG_KEEP_SUM) != 0;
+        sel.unroll = st->unroll;
+        sel.nontemporal = st->nontemporal;
+        const int64_t ntiles = tile_hi - tile_lo;
+        int64_t span = ntiles;
+        if (st->xcd_remap) span = ((ntiles + 7) / 8) * 8;
+        int64_t grid = span;
+        if (st->wg_per_cu > 0) {
+            int64_t cap = (int64_t)st->num_cus * st->wg_per_cu;
+            if (st->xcd_remap) cap = (cap + 7) / 8 * 8;
+            if (grid > cap) grid = cap;
+        }
+        if (grid > 0x7FFFFFF0LL) grid = 0x7FFFFFF0LL;       // multiple of 8; the tile loop strides
+        KV_HIP(st, kv_launch_fused(sel, a, (unsigned)grid, st->stream));
+        if ((int)st->log.size() < LOG_CAP) st->log.emplace_back(first, n);
+        else st->log[(size_t)(st->launches_total % LOG_CAP)] = std::make_pair(first, n);
+        ++st->launches_total;
+    }
+    for (int u = first; u < first + n; ++u) {
+        for (const Deferred& d : st->deferred[u]) {
+            int rc = issue_copy_out(st, d.key, d.dst, d.what);
+            if (rc != KV_OK) return rc;
+        }
+        st->deferred[u].clear();
+    }
+    return KV_OK;
+}
+
+int drain_chain(kv_store* st) {
+    int first = 0, n = 0;
+    while (st->chain.next_run(&first, &n)) {
+        int rc = launch_run(st, first, n);
+        if (rc != KV_OK) return rc;
+    }
+    return KV_OK;
+}
+
+int check_grads(kv_store* st, int key, const void* const* grads) {
+    if (!grads) {
+        set_err(st->err, "push of key %d: null gradient pointer array", key);
+        return KV_ERR_ARG;
+    }
+    const uintptr_t mask = (uintptr_t)st->plan.itemsize - 1;
+    for (int r = 0; r < st->W; ++r) {
+        if (!grads[r] && st->plan.numel[key] > 0) {
+            set_err(st->err, "push of key %d: gradient pointer of rank %d is null", key, r);
+            return KV_ERR_ARG;
+        }
+        if ((uintptr_t)grads[r] & mask) {
+            set_err(st->err, "push of key %d: gradient pointer of rank %d is not aligned to %d bytes", key, r,
+                    st->plan.itemsize);
+            return KV_ERR_ALIGN;
+        }
+    }
+    return KV_OK;
+}
+
+void record_grads(kv_store* st, int key, const void* const* grads) {
+    const size_t row = (size_t)st->plan.key_seg[key] * (size_t)st->W;
+    for (int r = 0; r < st->W; ++r) st->cur_ptrs[row + r] = grads[r];
+}
+
+int pull_common(kv_store* st, int key, void* dst, int what) {
+    if (!st) return KV_ERR_ARG;
+    int rc = check_key(st, key);
+    if (rc != KV_OK) return rc;
+    if (!dst && st->plan.numel[key] > 0) {
+        set_err(st->err, "pull of key %d: null destination", key);
+        return KV_ERR_ARG;
+    }
+    if (what == 2 && !(st->flags & KV_FLAG_KEEP_SUM)) {
+        set_err(st->err, "kv_pull_grad needs a store created with KV_FLAG_KEEP_SUM");
+        return KV_ERR_STATE;
+    }
+    if (st->chain.marked[key]) {               // pushed, unit not launched yet: run after that launch
+        st->deferred[st->plan.key_unit[key]].push_back(Deferred{key, dst, what});
+        return KV_OK;
+    }
+    return issue_copy_out(st, key, dst, what);
+}
+
+int set_common(kv_store* st, int key, const void* src, float* arena) {
+    if (!st) return KV_ERR_ARG;
+    int rc = check_key(st, key);
+    if (rc != KV_OK) return rc;
+    const int64_t n = st->plan.numel[key];
+    if (n == 0) return KV_OK;
+    if (!src) {
+        set_err(st->err, "set of key %d: null source", key);
+        return KV_ERR_ARG;
+    }
+    KV_HIP(st, hipMemcpyAsync(arena + st->plan.key_arena_off[key], src, (size_t)n * sizeof(float), hipMemcpyDefault,
+                              st->stream));
+    return KV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+// ------------------------------------------------------------------ plan
+int kv_plan_create(kv_plan** out, int num_keys, const int64_t* key_numel, int grad_dtype, size_t bucket_bytes) {
+    if (!out) {
+        set_err(g_err, "kv_plan_create: out is null");
+        return KV_ERR_ARG;
+    }
+    *out = nullptr;
+    kv_plan* p = new (std::nothrow) kv_plan();
+    if (!p) return KV_ERR_NOMEM;
+    int rc = KV_ERR_NOMEM;
+    try {
+        rc = kv_plan_build(*p, num_keys, key_numel, grad_dtype, bucket_bytes);
+    } catch (const std::bad_alloc&) {
+        rc = KV_ERR_NOMEM;
+    }
+    if (rc != KV_OK) {
+        set_err(g_err, "kv_plan_create: bad arguments (num_keys=%d, grad_dtype=%d, bucket_bytes=%zu)", num_keys,
+                grad_dtype, bucket_bytes);
+        delete p;
+        return rc;
+    }
+    *out = p;
+    return KV_OK;
+}
+
+void kv_plan_destroy(kv_plan* plan) { delete plan; }
+
+int kv_plan_num_keys(const kv_plan* plan) { return plan ? plan->num_keys : KV_ERR_ARG; }
+int kv_plan_num_units(const kv_plan* plan) { return plan ? (int)plan->units.size() : KV_ERR_ARG; }
+
+int kv_plan_unit(const kv_plan* plan, int unit, int* is_large_out, int* nkeys_out, int* keys_out, int cap) {
+    if (!plan || unit < 0 || unit >= (int)plan->units.size()) return KV_ERR_ARG;
+    const KvPlanUnit& u = plan->units[unit];
+    if (is_large_out) *is_large_out = u.large ? 1 : 0;
+    if (nkeys_out) *nkeys_out = (int)u.keys.size();
+    if (keys_out)
+        for (int i = 0; i < cap && i < (int)u.keys.size(); ++i) keys_out[i] = u.keys[i];
+    return KV_OK;
+}
+
+int kv_plan_key(const kv_plan* plan, int key, int* unit_out, int64_t* arena_offset_out) {
+    if (!plan) return KV_ERR_ARG;
+    if (key < 0 || key >= plan->num_keys) return KV_ERR_KEY;
+    if (unit_out) *unit_out = plan->key_unit[key];
+    if (arena_offset_out) *arena_offset_out = plan->key_arena_off[key];
+    return KV_OK;
+}
+
+int64_t kv_plan_arena_numel(const kv_plan* plan) { return plan ? plan->arena_numel : (int64_t)KV_ERR_ARG; }
+
+// ------------------------------------------------------------------ chain
+int kv_chain_create(kv_chain** out, const kv_plan* plan) {
+    if (!out || !plan) {
+        set_err(g_err, "kv_chain_create: null argument");
+        return KV_ERR_ARG;
+    }
+    kv_chain* c = new (std::nothrow) kv_chain();
+    if (!c) return KV_ERR_NOMEM;
+    c->reset(plan);
+    *out = c;
+    return KV_OK;
+}
+
+void kv_chain_destroy(kv_chain* chain) { delete chain; }
+int kv_chain_mark(kv_chain* chain, int key) { return chain ? chain->mark(key) : KV_ERR_ARG; }
+
+int kv_chain_next_run(kv_chain* chain, int* first_unit_out, int* n_units_out) {
+    if (!chain || !first_unit_out || !n_units_out) return KV_ERR_ARG;
+    return chain->next_run(first_unit_out, n_units_out) ? 1 : 0;
+}
+
+int kv_chain_pending_keys(const kv_chain* chain) { return chain ? chain->pending_keys : KV_ERR_ARG; }
+int kv_chain_next_unit(const kv_chain* chain) { return chain ? chain->next_unit : KV_ERR_ARG; }
+
+// ------------------------------------------------------------------ store
+int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dtype, int W, size_t bucket_bytes,
+            const kv_sgd_params* params, unsigned flags, const kv_tuning* tuning, void* hip_stream) {
+    if (!out) {
+        set_err(g_err, "kv_init: out is null");
+        return KV_ERR_ARG;
+    }
+    *out = nullptr;
+    if (!params || W < 1 || W > KV_MAX_W || (flags & ~(unsigned)KV_FLAG_KEEP_SUM)) {
+        set_err(g_err, "kv_init: bad arguments (params=%p, W=%d, flags=%u)", (const void*)params, W, flags);
+        return KV_ERR_ARG;
+    }
+    if (params->reduce_order != KV_REDUCE_SEQUENTIAL && params->reduce_order != KV_REDUCE_PAIRWISE) {
+        set_err(g_err, "kv_init: reduce_order %d unknown", params->reduce_order);
+        return KV_ERR_ARG;
+    }
+    kv_store* st = new (std::nothrow) kv_store();
+    if (!st) return KV_ERR_NOMEM;
+    int rc = kv_plan_build(st->plan, num_keys, key_numel, grad_dtype, bucket_bytes);
+    if (rc != KV_OK) {
+        set_err(g_err, "kv_init: bad key set (num_keys=%d, grad_dtype=%d, bucket_bytes=%zu)", num_keys, grad_dtype,
+                bucket_bytes);
+        delete st;
+        return rc;
+    }
+    st->chain.reset(&st->plan);
+    st->W = W;
+    st->flags = flags;
+    st->p = *params;
+    st->rescale = params->rescale > 0.0f ? params->rescale : 1.0f / (float)W;
+    st->stream = static_cast<hipStream_t>(hip_stream);
+
+    // defaults: two vectors per lane up to W = 8, one above
+    st->unroll = W <= 8 ? 2 : 1;
+    st->wg_per_cu = 0;
+    st->nontemporal = 1;
+    st->xcd_remap = 0;
+    if (tuning) {
+        if (tuning->unroll != 0) st->unroll = tuning->unroll;
+        if (tuning->workgroups_per_cu >= 0) st->wg_per_cu = tuning->workgroups_per_cu;
+        if (tuning->nontemporal >= 0) st->nontemporal = tuning->nontemporal ? 1 : 0;
+        if (tuning->xcd_remap >= 0) st->xcd_remap = tuning->xcd_remap ? 1 : 0;
+    }
+    if (st->unroll != 1 && st->unroll != 2 && st->unroll != 4) {
+        set_err(g_err, "kv_init: tuning.unroll must be 1, 2 or 4");
+        delete st;
+        return KV_ERR_ARG;
+    }
+    st->tile_elems = kv_tile_elems(grad_dtype == KV_F16, st->unroll);
+
+#define KV_INIT_HIP(call)                                                                     \
+    do {                                                                                      \
+        hipError_t e_ = (call);                                                               \
+        if (e_ != hipSuccess) {                                                               \
+            set_err(g_err, "kv_init: %s failed: %s", #call, hipGetErrorString(e_));           \
+            free_store(st);                                                                   \
+            return KV_ERR_HIP;                                                                \
+        }                                                                                     \
+    } while (0)
+
+    KV_INIT_HIP(hipGetDevice(&st->device));
+    int cus = 0;
+    KV_INIT_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, st->device));
+    if (cus > 0) st->num_cus = cus;
+
+    std::vector<KvTile> tiles;
+    std::vector<KvSeg> segs;
+    try {
+        kv_plan_tiles(st->plan, st->tile_elems, tiles, segs, st->unit_tile_begin);
+        st->table_elems = segs.size() * (size_t)W;
+        st->cur_ptrs.assign(st->table_elems, nullptr);
+        for (int i = 0; i < NSLOT; ++i) {
+            st->mirror[i].assign(st->table_elems, nullptr);
+            st->row_valid[i].assign(segs.size(), 0);
+        }
+        st->deferred.resize(st->plan.units.size());
+        st->log.reserve(64);
+    } catch (const std::bad_alloc&) {
+        set_err(g_err, "kv_init: out of host memory");
+        free_store(st);
+        return KV_ERR_NOMEM;
+    }
+
+    const size_t arena_bytes = (size_t)(st->plan.arena_numel > 0 ? st->plan.arena_numel : 4) * sizeof(float);
+    KV_INIT_HIP(hipMalloc((void**)&st->w, arena_bytes));
+    KV_INIT_HIP(hipMalloc((void**)&st->m, arena_bytes));
+    KV_INIT_HIP(hipMemsetAsync(st->w, 0, arena_bytes, st->stream));
+    KV_INIT_HIP(hipMemsetAsync(st->m, 0, arena_bytes, st->stream));
+    if (flags & KV_FLAG_KEEP_SUM) {
+        KV_INIT_HIP(hipMalloc((void**)&st->s, arena_bytes));
+        KV_INIT_HIP(hipMemsetAsync(st->s, 0, arena_bytes, st->stream));
+    }
+    const size_t tile_bytes = (tiles.empty() ? 1 : tiles.size()) * sizeof(KvTile);
+    const size_t seg_bytes = segs.size() * sizeof(KvSeg);
+    KV_INIT_HIP(hipMalloc((void**)&st->d_tiles, tile_bytes));
+    KV_INIT_HIP(hipMalloc((void**)&st->d_segs, seg_bytes));
+    if (!tiles.empty())
+        KV_INIT_HIP(hipMemcpyAsync(st->d_tiles, tiles.data(), tiles.size() * sizeof(KvTile), hipMemcpyHostToDevice, st->stream));
+    KV_INIT_HIP(hipMemcpyAsync(st->d_segs, segs.data(), seg_bytes, hipMemcpyHostToDevice, st->stream));
+    for (int i = 0; i < NSLOT; ++i) KV_INIT_HIP(hipMalloc((void**)&st->d_slot[i], st->table_elems * sizeof(void*)));
+    KV_INIT_HIP(hipHostMalloc((void**)&st->h_stage, (size_t)NSTAGE * st->table_elems * sizeof(void*), hipHostMallocDefault));
+    for (int i = 0; i < NSTAGE; ++i) KV_INIT_HIP(hipEventCreateWithFlags(&st->stage_ev[i], hipEventDisableTiming));
+    KV_INIT_HIP(hipEventCreate(&st->t0));
+    KV_INIT_HIP(hipEventCreate(&st->t1));
+    // the host vectors `tiles` and `segs` die at return: wait for their uploads
+    KV_INIT_HIP(hipStreamSynchronize(st->stream));
+#undef KV_INIT_HIP
+    *out = st;
+    return KV_OK;
+}
+
+void kv_destroy(kv_store* store) {
+    if (!store) return;
+    (void)hipStreamSynchronize(store->stream);
+    free_store(store);
+}
+
+int kv_set_weights(kv_store* store, int key, const void* src_f32) {
+    return store ? set_common(store, key, src_f32, store->w) : KV_ERR_ARG;
+}
+
+int kv_set_momentum(kv_store* store, int key, const void* src_f32) {
+    return store ? set_common(store, key, src_f32, store->m) : KV_ERR_ARG;
+}
+
+int kv_set_lr(kv_store* store, float lr) {
+    if (!store) return KV_ERR_ARG;
+    store->p.lr = lr;
+    return KV_OK;
+}
+
+int kv_push(kv_store* store, int key, const void* const* dev_grads) {
+    if (!store) return KV_ERR_ARG;
+    int rc = check_key(store, key);
+    if (rc != KV_OK) return rc;
+    rc = check_grads(store, key, dev_grads);
+    if (rc != KV_OK) return rc;
+    rc = store->chain.mark(key);
+    if (rc != KV_OK) {
+        set_err(store->err, "key %d pushed twice before its unit ran", key);
+        return rc;
+    }
+    record_grads(store, key, dev_grads);
+    return drain_chain(store);
+}
+
+int kv_push_list(kv_store* store, int nkeys, const int* keys, const void* const* dev_grads) {
+    if (!store) return KV_ERR_ARG;
+    if (nkeys < 0 || (nkeys > 0 && (!keys || !dev_grads))) {
+        set_err(store->err, "kv_push_list: bad arguments");
+        return KV_ERR_ARG;
+    }
+    // validate everything before marking anything
+    for (int i = 0; i < nkeys; ++i) {
+        int rc = check_key(store, keys[i]);
+        if (rc != KV_OK) return rc;
+        rc = check_grads(store, keys[i], dev_grads + (size_t)i * store->W);
+        if (rc != KV_OK) return rc;
+        if (store->chain.marked[keys[i]]) {
+            set_err(store->err, "key %d pushed twice before its unit ran", keys[i]);
+            return KV_ERR_STATE;
+        }
+    }
+    for (int i = 0; i < nkeys; ++i) {
+        if (store->chain.mark(keys[i]) != KV_OK) {          // duplicate inside the list: undo
+            for (int j = 0; j < i; ++j) {
+                store->chain.marked[keys[j]] = 0;
+                ++store->chain.pending[store->plan.key_unit[keys[j]]];
+                --store->chain.pending_keys;
+            }
+            set_err(store->err, "key %d appears twice in one push list", keys[i]);
+            return KV_ERR_STATE;
+        }
+    }
+    for (int i = 0; i < nkeys; ++i) record_grads(store, keys[i], dev_grads + (size_t)i * store->W);
+    return drain_chain(store);
+}
+
+int kv_pull(kv_store* store, int key, void* dev_out_f32) { return pull_common(store, key, dev_out_f32, 0); }
+int kv_pull_momentum(kv_store* store, int key, void* dev_out_f32) { return pull_common(store, key, dev_out_f32, 1); }
+int kv_pull_grad(kv_store* store, int key, void* dev_out_f32) { return pull_common(store, key, dev_out_f32, 2); }
+
+int kv_weights_ptr(kv_store* store, int key, void** dev_ptr_out) {
+    if (!store || !dev_ptr_out) return KV_ERR_ARG;
+    int rc = check_key(store, key);
+    if (rc != KV_OK) return rc;
+    *dev_ptr_out = store->w + store->plan.key_arena_off[key];
+    return KV_OK;
+}
+
+int kv_wait(kv_store* store, int key) {
+    if (!store) return KV_ERR_ARG;
+    if (key >= 0) {
+        int rc = check_key(store, key);
+        if (rc != KV_OK) return rc;
+        if (store->chain.marked[key]) {
+            set_err(store->err, "kv_wait: key %d is pushed but its unit waits for other keys or lower units", key);
+            return KV_ERR_INCOMPLETE;
+        }
+        KV_HIP(store, hipStreamSynchronize(store->stream));
+        return KV_OK;
+    }
+    if (key != -1) {
+        set_err(store->err, "kv_wait: key %d", key);
+        return KV_ERR_KEY;
+    }
+    KV_HIP(store, hipStreamSynchronize(store->stream));
+    for (int i = 0; i < NSTAGE; ++i) store->stage_busy[i] = false;
+    if (store->chain.pending_keys > 0 || store->chain.next_unit != 0) {
+        set_err(store->err, "kv_wait: iteration incomplete (%d keys pushed but not launched, next unit %d)",
+                store->chain.pending_keys, store->chain.next_unit);
+        return KV_ERR_INCOMPLETE;
+    }
+    return KV_OK;
+}
+
+const kv_plan* kv_store_plan(const kv_store* store) { return store ? &store->plan : nullptr; }
+
+int kv_launch_log(const kv_store* store, int64_t* total_out, int* first_unit_out, int* n_units_out, int cap) {
+    if (!store) return KV_ERR_ARG;
+    if (total_out) *total_out = store->launches_total;
+    if (cap <= 0 || !first_unit_out || !n_units_out) return KV_OK;
+    const int64_t have = (int64_t)store->log.size();
+    int64_t n = have < cap ? have : cap;
+    for (int64_t i = 0; i < n; ++i) {
+        const int64_t idx = store->launches_total - n + i;          // absolute launch number
+        const auto& e = store->log[(size_t)(idx % LOG_CAP)];
+        first_unit_out[i] = e.first;
+        n_units_out[i] = e.second;
+    }
+    return (int)n;
+}
+
+int kv_timing_begin(kv_store* store) {
+    if (!store) return KV_ERR_ARG;
+    KV_HIP(store, hipEventRecord(store->t0, store->stream));
+    store->launches_at_begin = store->launches_total;
+    store->timing_active = true;
+    return KV_OK;
+}
+
+int kv_timing_end(kv_store* store, float* ms_out, int64_t* launches_out) {
+    if (!store || !ms_out) return KV_ERR_ARG;
+    if (!store->timing_active) {
+        set_err(store->err, "kv_timing_end without kv_timing_begin");
+        return KV_ERR_STATE;
+    }
+    KV_HIP(store, hipEventRecord(store->t1, store->stream));
+    KV_HIP(store, hipEventSynchronize(store->t1));
+    KV_HIP(store, hipEventElapsedTime(ms_out, store->t0, store->t1));
+    if (launches_out) *launches_out = store->launches_total - store->launches_at_begin;
+    store->timing_active = false;
+    return KV_OK;
+}
+
+int kv_copy_bytes(void* dev_dst, const void* dev_src, size_t bytes, void* hip_stream) {
+    if (!dev_dst || !dev_src || (bytes & 15u) || ((uintptr_t)dev_dst & 15u) || ((uintptr_t)dev_src & 15u)) {
+        set_err(g_err, "kv_copy_bytes: pointers and size must be multiples of 16");
+        return KV_ERR_ARG;
+    }
+    hipError_t e = kv_launch_copy(dev_dst, dev_src, bytes, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) {
+        set_err(g_err, "kv_copy_bytes: %s", hipGetErrorString(e));
+        return KV_ERR_HIP;
+    }
+    return KV_OK;
+}
+
+const char* kv_last_error(const kv_store* store) { return store ? store->err.c_str() : g_err.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,342 @@
+"""ctypes binding of include/kv.h: argument marshalling only.
+
+Names follow the C ABI (kv_init -> KVStore(...), kv_push -> KVStore.push, ...).
+Tensors are torch tensors on the GPU; only their ``data_ptr()`` crosses the
+boundary.  PyTorch supplies device memory and the stream, nothing else.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+KV_F32, KV_F16 = 0, 1
+KV_REDUCE_SEQUENTIAL, KV_REDUCE_PAIRWISE = 0, 1
+KV_FLAG_KEEP_SUM = 1
+STATUS = {0: "KV_OK", -1: "KV_ERR_ARG", -2: "KV_ERR_KEY", -3: "KV_ERR_STATE", -4: "KV_ERR_ALIGN",
+          -5: "KV_ERR_INCOMPLETE", -6: "KV_ERR_HIP", -7: "KV_ERR_NOMEM"}
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libkv_mi355x.so")
+_lib: Optional[ctypes.CDLL] = None
+
+
+class KVError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+class _SgdParams(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("momentum", ctypes.c_float), ("wd", ctypes.c_float),
+                ("rescale", ctypes.c_float), ("reduce_order", ctypes.c_int)]
+
+
+class _Tuning(ctypes.Structure):
+    _fields_ = [("unroll", ctypes.c_int), ("workgroups_per_cu", ctypes.c_int), ("nontemporal", ctypes.c_int),
+                ("xcd_remap", ctypes.c_int)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads the built library.  It is never built or replaced by a fallback here."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_1802_06949_amd.build`")
+    L = ctypes.CDLL(_LIB_PATH)
+    c_int, c_i64, c_vp, c_sz = ctypes.c_int, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
+    P = ctypes.POINTER
+
+    def sig(name, res, *args):
+        fn = getattr(L, name)
+        fn.restype = res
+        fn.argtypes = list(args)
+
+    sig("kv_plan_create", c_int, P(c_vp), c_int, P(c_i64), c_int, c_sz)
+    sig("kv_plan_destroy", None, c_vp)
+    sig("kv_plan_num_keys", c_int, c_vp)
+    sig("kv_plan_num_units", c_int, c_vp)
+    sig("kv_plan_unit", c_int, c_vp, c_int, P(c_int), P(c_int), P(c_int), c_int)
+    sig("kv_plan_key", c_int, c_vp, c_int, P(c_int), P(c_i64))
+    sig("kv_plan_arena_numel", c_i64, c_vp)
+    sig("kv_chain_create", c_int, P(c_vp), c_vp)
+    sig("kv_chain_destroy", None, c_vp)
+    sig("kv_chain_mark", c_int, c_vp, c_int)
+    sig("kv_chain_next_run", c_int, c_vp, P(c_int), P(c_int))
+    sig("kv_chain_pending_keys", c_int, c_vp)
+    sig("kv_chain_next_unit", c_int, c_vp)
+    sig("kv_init", c_int, P(c_vp), c_int, P(c_i64), c_int, c_int, c_sz, P(_SgdParams), ctypes.c_uint, P(_Tuning), c_vp)
+    sig("kv_destroy", None, c_vp)
+    sig("kv_set_weights", c_int, c_vp, c_int, c_vp)
+    sig("kv_set_momentum", c_int, c_vp, c_int, c_vp)
+    sig("kv_set_lr", c_int, c_vp, ctypes.c_float)
+    sig("kv_push", c_int, c_vp, c_int, P(c_vp))
+    sig("kv_push_list", c_int, c_vp, c_int, P(c_int), P(c_vp))
+    sig("kv_pull", c_int, c_vp, c_int, c_vp)
+    sig("kv_pull_grad", c_int, c_vp, c_int, c_vp)
+    sig("kv_pull_momentum", c_int, c_vp, c_int, c_vp)
+    sig("kv_weights_ptr", c_int, c_vp, c_int, P(c_vp))
+    sig("kv_wait", c_int, c_vp, c_int)
+    sig("kv_store_plan", c_vp, c_vp)
+    sig("kv_launch_log", c_int, c_vp, P(c_i64), P(c_int), P(c_int), c_int)
+    sig("kv_timing_begin", c_int, c_vp)
+    sig("kv_timing_end", c_int, c_vp, P(ctypes.c_float), P(c_i64))
+    sig("kv_copy_bytes", c_int, c_vp, c_vp, c_sz, c_vp)
+    sig("kv_last_error", ctypes.c_char_p, c_vp)
+    _lib = L
+    return L
+
+
+def _dtype_code(grad_dtype) -> int:
+    if grad_dtype in (KV_F32, "f32", "float32"):
+        return KV_F32
+    if grad_dtype in (KV_F16, "f16", "float16"):
+        return KV_F16
+    raise ValueError(f"unknown gradient dtype {grad_dtype!r}")
+
+
+def _global_error(L) -> str:
+    return L.kv_last_error(None).decode()
+
+
+class Plan:
+    """kv_plan_*: the bucket plan (host only)."""
+
+    def __init__(self, key_numel: Sequence[int], grad_dtype="f32", bucket_bytes: int = 1 << 22, _borrowed=None):
+        self._L = load_library()
+        self._owned = _borrowed is None
+        if _borrowed is not None:
+            self._h = ctypes.c_void_p(_borrowed)
+            return
+        n = len(key_numel)
+        arr = (ctypes.c_int64 * max(n, 1))(*[int(x) for x in key_numel])
+        h = ctypes.c_void_p()
+        rc = self._L.kv_plan_create(ctypes.byref(h), n, arr, _dtype_code(grad_dtype), int(bucket_bytes))
+        if rc != 0:
+            raise KVError(rc, _global_error(self._L))
+        self._h = h
+
+    def __del__(self):
+        if getattr(self, "_owned", False) and getattr(self, "_h", None):
+            self._L.kv_plan_destroy(self._h)
+            self._h = None
+
+    @property
+    def num_keys(self) -> int:
+        return self._L.kv_plan_num_keys(self._h)
+
+    @property
+    def num_units(self) -> int:
+        return self._L.kv_plan_num_units(self._h)
+
+    @property
+    def arena_numel(self) -> int:
+        return self._L.kv_plan_arena_numel(self._h)
+
+    def unit(self, u: int) -> Tuple[List[int], bool]:
+        large, nk = ctypes.c_int(), ctypes.c_int()
+        rc = self._L.kv_plan_unit(self._h, u, ctypes.byref(large), ctypes.byref(nk), None, 0)
+        if rc != 0:
+            raise KVError(rc, f"unit {u}")
+        keys = (ctypes.c_int * max(nk.value, 1))()
+        self._L.kv_plan_unit(self._h, u, None, None, keys, nk.value)
+        return list(keys[:nk.value]), bool(large.value)
+
+    def units(self) -> List[Tuple[List[int], bool]]:
+        return [self.unit(u) for u in range(self.num_units)]
+
+    def key(self, k: int) -> Tuple[int, int]:
+        unit, off = ctypes.c_int(), ctypes.c_int64()
+        rc = self._L.kv_plan_key(self._h, k, ctypes.byref(unit), ctypes.byref(off))
+        if rc != 0:
+            raise KVError(rc, f"key {k}")
+        return unit.value, off.value
+
+
+class Chain:
+    """kv_chain_*: the launch-order state machine (host only)."""
+
+    def __init__(self, plan: Plan):
+        self._L = load_library()
+        self._plan = plan
+        h = ctypes.c_void_p()
+        rc = self._L.kv_chain_create(ctypes.byref(h), plan._h)
+        if rc != 0:
+            raise KVError(rc, _global_error(self._L))
+        self._h = h
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            self._L.kv_chain_destroy(self._h)
+            self._h = None
+
+    def mark(self, key: int) -> int:
+        return self._L.kv_chain_mark(self._h, key)
+
+    def next_run(self) -> Optional[Tuple[int, int]]:
+        first, n = ctypes.c_int(), ctypes.c_int()
+        return (first.value, n.value) if self._L.kv_chain_next_run(self._h, ctypes.byref(first), ctypes.byref(n)) == 1 else None
+
+    def drain(self) -> List[Tuple[int, int]]:
+        runs = []
+        while True:
+            r = self.next_run()
+            if r is None:
+                return runs
+            runs.append(r)
+
+    @property
+    def pending_keys(self) -> int:
+        return self._L.kv_chain_pending_keys(self._h)
+
+    @property
+    def next_unit(self) -> int:
+        return self._L.kv_chain_next_unit(self._h)
+
+
+class PushList:
+    """Pre-marshalled arguments of kv_push_list; keeps the tensors alive."""
+
+    def __init__(self, W: int, keys: Sequence[int], grads: Sequence[Sequence]):
+        if len(keys) != len(grads):
+            raise ValueError("one gradient list per key expected")
+        self.n = len(keys)
+        self.keys = (ctypes.c_int * max(self.n, 1))(*[int(k) for k in keys])
+        flat = []
+        for g in grads:
+            if len(g) != W:
+                raise ValueError(f"expected {W} gradient copies per key")
+            flat.extend(int(t.data_ptr()) for t in g)
+        self.ptrs = (ctypes.c_void_p * max(len(flat), 1))(*flat)
+        self._keep = grads
+
+
+class KVStore:
+    """kv_init ... kv_destroy."""
+
+    def __init__(self, key_numel: Sequence[int], W: int, grad_dtype="f32", bucket_bytes: int = 1 << 22, *,
+                 lr: float, momentum: float = 0.0, wd: float = 0.0, rescale: float = 0.0,
+                 reduce_order: int = KV_REDUCE_SEQUENTIAL, keep_sum: bool = False, stream: Optional[int] = None,
+                 unroll: int = 0, workgroups_per_cu: int = -1, nontemporal: int = -1, xcd_remap: int = -1):
+        self._L = load_library()
+        self._h = None
+        self.key_numel = [int(x) for x in key_numel]
+        self.W = int(W)
+        self.grad_dtype = _dtype_code(grad_dtype)
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        self.stream = int(stream)
+        n = len(self.key_numel)
+        arr = (ctypes.c_int64 * max(n, 1))(*self.key_numel)
+        p = _SgdParams(lr, momentum, wd, rescale, reduce_order)
+        t = _Tuning(unroll, workgroups_per_cu, nontemporal, xcd_remap)
+        h = ctypes.c_void_p()
+        rc = self._L.kv_init(ctypes.byref(h), n, arr, self.grad_dtype, self.W, int(bucket_bytes), ctypes.byref(p),
+                             KV_FLAG_KEEP_SUM if keep_sum else 0, ctypes.byref(t), ctypes.c_void_p(self.stream))
+        if rc != 0:
+            raise KVError(rc, _global_error(self._L))
+        self._h = h
+        self.plan = Plan([], _borrowed=self._L.kv_store_plan(h))
+
+    def close(self) -> None:
+        if self._h is not None:
+            self._L.kv_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int) -> None:
+        if rc != 0:
+            raise KVError(rc, self._L.kv_last_error(self._h).decode())
+
+    # --- values
+    def set_weights(self, key: int, src) -> None:
+        self._check(self._L.kv_set_weights(self._h, key, ctypes.c_void_p(src.data_ptr())))
+
+    def set_momentum(self, key: int, src) -> None:
+        self._check(self._L.kv_set_momentum(self._h, key, ctypes.c_void_p(src.data_ptr())))
+
+    def set_lr(self, lr: float) -> None:
+        self._check(self._L.kv_set_lr(self._h, lr))
+
+    # --- push
+    def push(self, key: int, grads: Sequence) -> None:
+        if len(grads) != self.W:
+            raise ValueError(f"expected {self.W} gradient copies")
+        ptrs = (ctypes.c_void_p * self.W)(*[int(g.data_ptr()) for g in grads])
+        self._check(self._L.kv_push(self._h, key, ptrs))
+
+    def push_raw(self, key: int, ptrs: Sequence[int]) -> int:
+        """kv_push with raw addresses; returns the status instead of raising."""
+        arr = (ctypes.c_void_p * max(len(ptrs), 1))(*[int(p) for p in ptrs])
+        return self._L.kv_push(self._h, key, arr)
+
+    def make_push_list(self, keys: Sequence[int], grads: Sequence[Sequence]) -> PushList:
+        return PushList(self.W, keys, grads)
+
+    def push_list(self, pl: PushList) -> None:
+        self._check(self._L.kv_push_list(self._h, pl.n, pl.keys, pl.ptrs))
+
+    # --- pull
+    def pull(self, key: int, out) -> None:
+        self._check(self._L.kv_pull(self._h, key, ctypes.c_void_p(out.data_ptr())))
+
+    def pull_grad(self, key: int, out) -> None:
+        self._check(self._L.kv_pull_grad(self._h, key, ctypes.c_void_p(out.data_ptr())))
+
+    def pull_momentum(self, key: int, out) -> None:
+        self._check(self._L.kv_pull_momentum(self._h, key, ctypes.c_void_p(out.data_ptr())))
+
+    def weights_ptr(self, key: int) -> int:
+        p = ctypes.c_void_p()
+        self._check(self._L.kv_weights_ptr(self._h, key, ctypes.byref(p)))
+        return int(p.value or 0)
+
+    def wait(self, key: int = -1) -> None:
+        self._check(self._L.kv_wait(self._h, key))
+
+    def wait_status(self, key: int = -1) -> int:
+        return self._L.kv_wait(self._h, key)
+
+    # --- introspection
+    def launch_log(self, cap: int = 4096) -> Tuple[int, List[Tuple[int, int]]]:
+        total = ctypes.c_int64()
+        first = (ctypes.c_int * cap)()
+        nun = (ctypes.c_int * cap)()
+        n = self._L.kv_launch_log(self._h, ctypes.byref(total), first, nun, cap)
+        if n < 0:
+            raise KVError(n, "kv_launch_log")
+        return total.value, [(first[i], nun[i]) for i in range(n)]
+
+    def timing_begin(self) -> None:
+        self._check(self._L.kv_timing_begin(self._h))
+
+    def timing_end(self) -> Tuple[float, int]:
+        ms, n = ctypes.c_float(), ctypes.c_int64()
+        self._check(self._L.kv_timing_end(self._h, ctypes.byref(ms), ctypes.byref(n)))
+        return ms.value, n.value
+
+    def last_error(self) -> str:
+        return self._L.kv_last_error(self._h).decode()
+
+
+def copy_bytes(dst, src, nbytes: int, stream: Optional[int] = None) -> None:
+    """kv_copy_bytes: the plain streaming copy kernel used to calibrate byte counters."""
+    L = load_library()
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    rc = L.kv_copy_bytes(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()), int(nbytes),
+                         ctypes.c_void_p(int(stream)))
+    if rc != 0:
+        raise KVError(rc, _global_error(L))

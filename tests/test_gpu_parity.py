@@ -1,0 +1,388 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle,
+element by element on the same seeded inputs.
+
+Bar: bit-exact raw sums, weights and momentum (same operation order on both
+sides, IEEE binary32, one rounding per operation).  This is stricter than the
+1e-6 (fp32) / 1e-3 (fp16 gradients) relative tolerances the target allows, so
+those are not used.  NaN payloads are the one exception (both sides NaN).
+"""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import kv_oracle as orc
+from tests.gpu_harness import Pair, run_config, same_bits_or_both_nan, to_device
+from tests.helpers import load_hand_cases
+
+pytestmark = pytest.mark.gpu
+F = np.float32
+
+
+def _rng(*seed):
+    return np.random.Generator(np.random.SFC64(list(seed)))
+
+
+def _grads(numel, W, dtype, seed, scale=0.01):
+    out = []
+    for k, n in enumerate(numel):
+        gk = [(_rng(seed, k, r).standard_normal(n, dtype=F) * F(scale)).astype(F) for r in range(W)]
+        if dtype == "f16":
+            gk = [g.astype(np.float16) for g in gk]
+        out.append(gk)
+    return out
+
+
+# Lengths that straddle the vector width, the wavefront, the workgroup and the
+# tile sizes (1024 / 2048 / 4096 fp32, 2048 / 4096 / 8192 fp16), plus empty keys.
+RAGGED = [0, 1, 2, 3, 4, 5, 7, 8, 9, 63, 64, 65, 255, 256, 257, 1023, 1024, 1025, 2047, 2048, 2049,
+          4095, 4096, 4097, 8191, 8192, 8193, 0, 12289, 20000]
+
+
+# ------------------------------------------------------------------ benchmark configurations
+@pytest.mark.parametrize("order", [orc.SEQUENTIAL, orc.PAIRWISE])
+@pytest.mark.parametrize("mode", ["list", "each"])
+def test_config1_mlp(order, mode):
+    run_config(wl.get_config(1), 3, order=order, mode=mode)
+
+
+@pytest.mark.parametrize("order", [orc.SEQUENTIAL, orc.PAIRWISE])
+@pytest.mark.parametrize("mode", ["list", "each"])
+def test_config2_resnet20(order, mode):
+    run_config(wl.get_config(2), 3, order=order, mode=mode)
+
+
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("order", [orc.SEQUENTIAL, orc.PAIRWISE])
+def test_config3_resnet50_full_size(order):
+    """Full 25.6M-parameter key set, W = 8, in the launch configuration the
+    benchmark times (list push, default tuning, raw sums not stored)."""
+    run_config(wl.get_config(3), 3, order=order, keep_sum=(order == orc.PAIRWISE), gen_threads=16, oracle_threads=8)
+
+
+@pytest.mark.timeout(300)
+def test_config4_resnet50_half_gradients_full_size():
+    run_config(wl.get_config(4), 2, gen_threads=16, oracle_threads=8)
+
+
+@pytest.mark.timeout(600)
+def test_config5_vgg16_full_size():
+    """138M parameters, W = 16: one freshly generated step and a second one that
+    reuses those gradients with the ranks rotated (so that m != 0 is covered
+    without another 2.2e9 normal draws)."""
+    run_config(wl.get_config(5), 2, keep_sum=False, gen_threads=16, oracle_threads=8, rotate_after_first=True)
+
+
+# ------------------------------------------------------------------ ragged sizes, every W path
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("W", [1, 2, 3, 4, 5, 7, 8, 9, 13, 16, 32, 33])
+@pytest.mark.parametrize("order", [orc.SEQUENTIAL, orc.PAIRWISE])
+def test_ragged_keys_all_rank_counts(dtype, W, order):
+    pair = Pair(RAGGED, W, dtype, 16 << 10, lr=0.1, momentum=0.9, wd=1e-4, order=order)
+    try:
+        pair.set_weights([_rng(1, k).standard_normal(n, dtype=F) for k, n in enumerate(RAGGED)])
+        for t in range(2):
+            pair.step(_grads(RAGGED, W, dtype, 100 + t))
+            pair.compare(f"W={W} {dtype} order={order} step {t}")
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("unroll", [1, 2, 4])
+@pytest.mark.parametrize("tuning", [dict(), dict(workgroups_per_cu=1), dict(xcd_remap=1), dict(nontemporal=0),
+                                    dict(workgroups_per_cu=2, xcd_remap=1)])
+def test_tuning_never_changes_a_bit(dtype, unroll, tuning):
+    numel = RAGGED + [70001]
+    pair = Pair(numel, 8, dtype, 64 << 10, lr=0.1, momentum=0.9, wd=1e-4, unroll=unroll, **tuning)
+    try:
+        pair.set_weights([_rng(2, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        for t in range(2):
+            pair.step(_grads(numel, 8, dtype, 200 + t))
+            pair.compare(f"unroll={unroll} {tuning} step {t}")
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("dtype,misalign", [("f32", 1), ("f32", 3), ("f16", 1), ("f16", 4), ("f16", 7)])
+def test_gradient_buffers_not_16_byte_aligned(dtype, misalign):
+    """Views into a flat buffer: aligned to the element only, so the single-element path runs."""
+    numel = [5, 1000, 4096, 9001]
+    pair = Pair(numel, 4, dtype, 8 << 10, lr=0.1, momentum=0.9, wd=1e-4)
+    try:
+        pair.set_weights([_rng(3, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        for t in range(2):
+            pair.step(_grads(numel, 4, dtype, 300 + t), misalign=misalign)
+            pair.compare(f"misalign={misalign} step {t}")
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("bucket", [1, 4096, 1 << 40])
+def test_bucket_size_never_changes_a_bit(bucket):
+    numel = [10, 3000, 64, 1024, 5000, 7, 256]
+    pair = Pair(numel, 8, "f32", bucket, lr=0.1, momentum=0.9, wd=1e-4)
+    try:
+        pair.set_weights([_rng(4, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        for t in range(2):
+            pair.step(_grads(numel, 8, "f32", 400 + t))
+            pair.compare(f"bucket={bucket} step {t}")
+    finally:
+        pair.close()
+
+
+# ------------------------------------------------------------------ worked examples and special values
+@pytest.mark.parametrize("case", load_hand_cases(), ids=lambda c: c["name"])
+def test_hand_computed_cases_on_gpu(case):
+    dt = np.float32 if case["dtype"] == "f32" else np.float16
+    g = [np.array(r, dtype=dt) for r in case["g"]]
+    n = len(case["w"])
+    pair = Pair([n], len(g), case["dtype"], 4096, lr=case["lr"], momentum=case["momentum"], wd=case["wd"],
+                rescale=case["rescale"], order=case["order"])
+    try:
+        pair.set_weights([np.array(case["w"], dtype=F)])
+        pair.set_momentum([np.array(case["m"], dtype=F)])
+        pair.step([g])
+        assert np.array_equal(pair.fetch("s", 0), np.array(case["expect_s"], dtype=F))
+        assert np.array_equal(pair.fetch("m", 0), np.array(case["expect_m"], dtype=F))
+        assert np.array_equal(pair.fetch("w", 0), np.array(case["expect_w"], dtype=F))
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("W", [1, 2, 3, 4, 8])
+def test_kvstore_snippet_on_gpu(W):
+    """KVStore API section: every worker pushes ones((2,3)); pull returns W * ones."""
+    pair = Pair([6], W, "f32", 4096, lr=0.1, momentum=0.0, wd=0.0)
+    try:
+        pair.step([[np.ones(6, dtype=F) for _ in range(W)]])
+        assert np.array_equal(pair.fetch("s", 0), np.full(6, W, dtype=F))
+    finally:
+        pair.close()
+
+
+def test_every_half_bit_pattern_widens_exactly():
+    h = np.arange(65536, dtype=np.uint32).astype(np.uint16).view(np.float16)
+    pair = Pair([65536], 1, "f16", 1 << 20, lr=0.0, momentum=0.0, wd=0.0, rescale=1.0)
+    try:
+        pair.step([[h]])
+        pair.compare("all halves")
+        with np.errstate(invalid="ignore"):
+            ref = h.astype(np.float32)
+        assert same_bits_or_both_nan(pair.fetch("s", 0), ref)
+    finally:
+        pair.close()
+
+
+def test_subnormals_signed_zeros_inf_nan():
+    tiny = np.array([1, 2, 0x007FFFFF, 0x80000001], dtype=np.uint32).view(F)
+    special = np.array([-0.0, 0.0, np.inf, -np.inf, np.nan, 1e-45, -1e-45, 3e38], dtype=F)
+    g0 = np.concatenate([tiny, special, np.full(4, -0.0, dtype=F)])
+    g1 = np.concatenate([tiny, special[::-1], np.full(4, -0.0, dtype=F)])
+    n = g0.size
+    for order in (orc.SEQUENTIAL, orc.PAIRWISE):
+        pair = Pair([n], 2, "f32", 4096, lr=1.0, momentum=0.5, wd=0.0, rescale=1.0, order=order)
+        try:
+            pair.set_weights([np.linspace(-1, 1, n).astype(F) * F(1e-40)])
+            pair.set_momentum([np.full(n, 1e-42, dtype=F)])
+            with np.errstate(all="ignore"):
+                pair.step([[g0, g1]])
+            pair.compare("special values")
+            s = pair.fetch("s", 0)
+            assert np.all(s[-4:].view(np.uint32) == 0x80000000)       # -0 + -0 stays -0
+            assert s.view(np.uint32)[0] == 2                          # subnormal sum is kept
+        finally:
+            pair.close()
+
+
+def test_operations_are_not_fused_on_gpu():
+    a = F(1 + 2.0 ** -12)
+    pair = Pair([1], 1, "f32", 4096, lr=1.0, momentum=float(a), wd=0.0, rescale=1.0)
+    try:
+        pair.set_momentum([np.array([a], dtype=F)])
+        pair.step([[np.array([1 + 2.0 ** -11], dtype=F)]])
+        assert pair.fetch("m", 0)[0] == 0.0                          # a fused multiply-add would leave 2^-24
+        pair.compare("no fma")
+    finally:
+        pair.close()
+
+
+# ------------------------------------------------------------------ ordering, chain, pulls
+def test_push_order_changes_nothing_and_launches_ascend():
+    cfg = wl.get_config(2)
+    K = len(cfg.keys)
+    weights = wl.make_weights(cfg)
+    grads = [wl.make_step_gradients(cfg, t) for t in range(2)]
+    orders = [list(range(K)), list(range(K))[::-1], [int(x) for x in _rng(5).permutation(K)]]
+    results = []
+    for o in orders:
+        pair = Pair(cfg.numel, cfg.W, "f32", cfg.bucket_bytes, lr=cfg.lr, momentum=cfg.momentum, wd=cfg.wd)
+        try:
+            pair.set_weights(weights)
+            for t in range(2):
+                pair.step(grads[t], mode="each", order=o)
+            pair.compare(f"order {o[:4]}...")
+            total, log = pair.gpu.launch_log()
+            U = pair.gpu.plan.num_units
+            covered = []
+            for first, n in log:
+                covered += list(range(first, first + n))
+            assert covered == list(range(U)) * 2, "every unit once per iteration, ascending"
+            results.append([pair.fetch("w", k) for k in range(K)])
+        finally:
+            pair.close()
+    for r in results[1:]:
+        for a, b in zip(r, results[0]):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+def test_list_push_is_one_launch_per_iteration():
+    cfg = wl.get_config(2)
+    pair = Pair(cfg.numel, cfg.W, "f32", cfg.bucket_bytes, lr=cfg.lr, momentum=cfg.momentum, wd=cfg.wd)
+    try:
+        g = wl.make_step_gradients(cfg, 0)
+        dev = pair.step(g)
+        pair.step(g, dev=dev)
+        total, log = pair.gpu.launch_log()
+        assert total == 2 and log == [(0, pair.gpu.plan.num_units)] * 2
+    finally:
+        pair.close()
+
+
+def test_alternating_gradient_buffers_use_the_right_pointers():
+    """The device pointer tables are cached; cycling through more buffer sets than
+    there are cached tables must still read the set that was pushed."""
+    numel = [100, 5000, 64, 3000]
+    W = 2
+    pair = Pair(numel, W, "f32", 4096, lr=0.1, momentum=0.9, wd=1e-4)
+    try:
+        sets = [_grads(numel, W, "f32", 500 + i) for i in range(6)]
+        devs = [pair.upload(s) for s in sets]
+        seq = [0, 1, 0, 1, 2, 3, 4, 5, 0, 5, 2, 2, 1]
+        for i, which in enumerate(seq):
+            mode = "each" if i % 3 == 2 else "list"
+            pair.step(sets[which], dev=devs[which], mode=mode)
+            pair.compare(f"alternation step {i} set {which}")
+    finally:
+        pair.close()
+
+
+def test_pull_before_the_bucket_is_complete_is_deferred():
+    import torch
+    numel = [8, 8, 8]                                   # one bucket
+    pair = Pair(numel, 2, "f32", 4096, lr=0.5, momentum=0.0, wd=0.0)
+    try:
+        g = _grads(numel, 2, "f32", 600, scale=1.0)
+        dev = pair.upload(g)
+        out = torch.full((8,), 7.0, device="cuda")
+        pair.gpu.push(0, dev[0])
+        pair.gpu.pull(0, out)                           # unit not launched yet: queued
+        assert pair.gpu.wait_status(0) == -5            # KV_ERR_INCOMPLETE, does not block
+        assert pair.gpu.wait_status(-1) == -5
+        assert torch.all(out == 7.0)
+        pair.gpu.push(2, dev[2])
+        pair.gpu.push(1, dev[1])                        # completes the bucket: launch, then the queued pull
+        pair.gpu.wait()
+        pair.cpu.step(g)
+        assert np.array_equal(out.cpu().numpy(), pair.cpu.w[0])
+        pair.compare("deferred pull")
+    finally:
+        pair.close()
+
+
+def test_large_key_waits_for_lower_units():
+    """Chain order: a ready unit still waits for every lower unit."""
+    numel = [16, 4096, 16]                               # bucket {0, 2} is unit 0, key 1 (large) is unit 1
+    pair = Pair(numel, 2, "f32", 1024, lr=0.1, momentum=0.0, wd=0.0)
+    try:
+        assert pair.gpu.plan.units() == [([0, 2], False), ([1], True)]
+        g = _grads(numel, 2, "f32", 700)
+        dev = pair.upload(g)
+        pair.gpu.push(1, dev[1])
+        assert pair.gpu.launch_log()[0] == 0
+        pair.gpu.push(0, dev[0])
+        assert pair.gpu.launch_log()[0] == 0
+        pair.gpu.push(2, dev[2])
+        total, log = pair.gpu.launch_log()
+        assert total == 1 and log == [(0, 2)]
+        pair.gpu.wait()
+        pair.cpu.step(g)
+        pair.compare("chain")
+    finally:
+        pair.close()
+
+
+def test_errors_leave_the_store_usable():
+    import torch
+    kv = pytest.importorskip("paper_1802_06949_amd")
+    numel = [16, 16]
+    pair = Pair(numel, 2, "f32", 4096, lr=0.1, momentum=0.0, wd=0.0, keep_sum=False)
+    try:
+        g = _grads(numel, 2, "f32", 800)
+        dev = pair.upload(g)
+        ptrs0 = [t.data_ptr() for t in dev[0]]
+        assert pair.gpu.push_raw(5, ptrs0) == -2                        # KV_ERR_KEY
+        assert pair.gpu.push_raw(0, [ptrs0[0] + 2, ptrs0[1]]) == -4     # KV_ERR_ALIGN
+        assert pair.gpu.push_raw(0, [0, ptrs0[1]]) == -1                # KV_ERR_ARG
+        assert pair.gpu.push_raw(0, ptrs0) == 0
+        assert pair.gpu.push_raw(0, ptrs0) == -3                        # KV_ERR_STATE: second push
+        assert "twice" in pair.gpu.last_error()
+        with pytest.raises(kv.KVError):
+            pair.gpu.pull_grad(0, torch.empty(16, device="cuda"))       # store has no raw-sum arena
+        with pytest.raises(kv.KVError):
+            pair.gpu.push_list(pair.gpu.make_push_list([1, 1], [dev[1], dev[1]]))
+        pair.gpu.push(1, dev[1])
+        pair.gpu.wait()
+        pair.cpu.step(g)
+        pair.compare("after errors")
+    finally:
+        pair.close()
+
+
+def test_learning_rate_change_and_checkpoint_round_trip():
+    numel = [100, 3000, 17]
+    W = 4
+    a = Pair(numel, W, "f32", 4096, lr=0.1, momentum=0.9, wd=1e-4)
+    b = None
+    try:
+        a.set_weights([_rng(6, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        a.step(_grads(numel, W, "f32", 900))
+        a.gpu.set_lr(0.01); a.cpu.lr = 0.01
+        a.step(_grads(numel, W, "f32", 901))
+        a.compare("after lr change")
+        # save, restore into a fresh store, continue: bit-identical to continuing in place
+        w = [a.fetch("w", k) for k in range(len(numel))]
+        m = [a.fetch("m", k) for k in range(len(numel))]
+        b = Pair(numel, W, "f32", 4096, lr=0.01, momentum=0.9, wd=1e-4)
+        b.set_weights(w); b.set_momentum(m)
+        g = _grads(numel, W, "f32", 902)
+        a.step(g); b.step(g)
+        b.compare("restored")
+        for k in range(len(numel)):
+            assert np.array_equal(a.fetch("w", k).view(np.uint32), b.fetch("w", k).view(np.uint32))
+    finally:
+        a.close()
+        if b is not None:
+            b.close()
+
+
+def test_zero_copy_weights_pointer_and_timing():
+    import ctypes
+    import torch
+    numel = [64, 5000]
+    pair = Pair(numel, 2, "f32", 4096, lr=0.1, momentum=0.0, wd=0.0)
+    try:
+        g = _grads(numel, 2, "f32", 1000)
+        pair.gpu.timing_begin()
+        pair.step(g)
+        ms, launches = pair.gpu.timing_end()
+        assert launches == 1 and ms > 0
+        ptr = pair.gpu.weights_ptr(1)
+        assert ptr % 16 == 0
+        out = torch.empty(5000, device="cuda")
+        pair.kv.copy_bytes(out, type("P", (), {"data_ptr": lambda self: ptr})(), 5000 * 4)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), pair.cpu.w[1])
+    finally:
+        pair.close()

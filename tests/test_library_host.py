@@ -1,0 +1,134 @@
+"""CPU-only tests of the built library: exported symbols, the bucket plan against
+the oracle's plain scan, and the launch-order chain.  No compute call is made."""
+from __future__ import annotations
+
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import kv_oracle as orc
+
+kv = pytest.importorskip("paper_1802_06949_amd")
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _rng(*seed):
+    return np.random.Generator(np.random.SFC64(list(seed)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "kv.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = sorted(set(re.findall(r"\b(kv_[a-z_0-9]+)\s*\(", header)))
+    assert len(names) >= 30
+    lib = ctypes.CDLL(kv.library_path())
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in include/kv.h but not exported"
+
+
+def test_binding_covers_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "kv.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(kv_[a-z_0-9]+)\s*\(", header))
+    src = open(os.path.join(ROOT, "paper_1802_06949_amd", "kvstore.py")).read()
+    for n in names:
+        assert f'"{n}"' in src, f"{n} has no ctypes signature in the binding"
+
+
+def _lib_plan(numel, dtype, bucket):
+    p = kv.Plan(numel, dtype, bucket)
+    return p, p.units()
+
+
+@pytest.mark.parametrize("cfg_id", [1, 2, 3, 4, 5])
+def test_plan_matches_oracle_scan_on_benchmark_configs(cfg_id):
+    cfg = wl.get_config(cfg_id)
+    p, units = _lib_plan(cfg.numel, cfg.grad_dtype, cfg.bucket_bytes)
+    ref = orc.plan_units(cfg.numel, cfg.grad_itemsize, cfg.bucket_bytes)
+    assert units == [(u.keys, u.large) for u in ref]
+    off = orc.arena_offsets(cfg.numel, ref)
+    assert [p.key(k)[1] for k in range(len(cfg.numel))] == off
+    assert [p.key(k)[0] for k in range(len(cfg.numel))] == [i for k in range(len(cfg.numel))
+                                                            for i, u in enumerate(ref) if k in u.keys]
+    assert p.arena_numel >= max(o + n for o, n in zip(off, cfg.numel))
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_plan_matches_oracle_scan_on_random_key_sets(seed):
+    r = _rng(77, seed)
+    K = int(r.integers(1, 60))
+    numel = [int(x) for x in r.choice([0, 1, 3, 10, 64, 100, 255, 256, 257, 1000, 4096, 5000, 70000], size=K)]
+    dtype = ["f32", "f16"][seed % 2]
+    bucket = int(r.choice([1, 2, 4, 40, 1024, 1028, 4096, 16384, 1 << 20, 1 << 40]))
+    p, units = _lib_plan(numel, dtype, bucket)
+    ref = orc.plan_units(numel, 4 if dtype == "f32" else 2, bucket)
+    assert units == [(u.keys, u.large) for u in ref]
+    assert [p.key(k)[1] for k in range(K)] == orc.arena_offsets(numel, ref)
+
+
+def test_plan_rejects_bad_arguments():
+    for args in [([], "f32", 1024), ([10, -1], "f32", 1024), ([10], "f32", 0)]:
+        with pytest.raises(kv.KVError) as e:
+            kv.Plan(*args)
+        assert e.value.status == -1
+    with pytest.raises(ValueError):
+        kv.Plan([10], "f64", 1024)
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_chain_runs_ascend_whatever_the_push_order(seed):
+    """The paper's ordering requirement: the order in which units run is the same
+    whatever order the gradients become ready in."""
+    r = _rng(78, seed)
+    cfg = wl.get_config(int(r.integers(1, 6)))
+    p = kv.Plan(cfg.numel, cfg.grad_dtype, cfg.bucket_bytes)
+    c = kv.Chain(p)
+    K, U = p.num_keys, p.num_units
+    for it in range(3):
+        covered = []
+        for k in r.permutation(K):
+            assert c.mark(int(k)) == 0
+            for first, n in c.drain():
+                assert n >= 1
+                covered += list(range(first, first + n))
+                # a unit only runs once all its keys are in
+            assert covered == list(range(len(covered)))
+        assert covered == list(range(U))
+        assert c.pending_keys == 0 and c.next_unit == 0
+
+
+def test_chain_in_order_list_is_one_run():
+    cfg = wl.get_config(3)
+    p = kv.Plan(cfg.numel, cfg.grad_dtype, cfg.bucket_bytes)
+    c = kv.Chain(p)
+    for k in range(p.num_keys):
+        assert c.mark(k) == 0
+    assert c.drain() == [(0, p.num_units)]
+
+
+def test_chain_rejects_second_push_until_the_unit_ran():
+    p = kv.Plan([16, 4096, 16], "f32", 1024)            # unit 0 = {0, 2}, unit 1 = {1}
+    c = kv.Chain(p)
+    assert c.mark(1) == 0 and c.drain() == []           # ready, but waits for unit 0
+    assert c.mark(1) == -3
+    assert c.mark(0) == 0 and c.drain() == []
+    assert c.mark(7) == -2
+    assert c.pending_keys == 2 and c.next_unit == 0
+    assert c.mark(2) == 0 and c.drain() == [(0, 2)]
+    # next iteration may start on a unit that already ran while others are pending
+    assert c.mark(0) == 0 and c.mark(2) == 0
+    assert c.drain() == [(0, 1)] and c.next_unit == 1
+    assert c.mark(0) == 0 and c.drain() == []           # unit 0 of the following iteration: accepted, waits
+    assert c.mark(2) == 0 and c.mark(1) == 0
+    assert c.drain() == [(1, 1), (0, 1)]                # finishes the iteration, then wraps
+
+
+@pytest.mark.skipif(__import__("torch").cuda.is_available(), reason="checks the no-GPU failure path")
+def test_init_fails_loudly_without_a_gpu():
+    with pytest.raises(kv.KVError) as e:
+        kv.KVStore([10, 20], 2, lr=0.1, stream=0)
+    assert e.value.status == -6
