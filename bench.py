@@ -37,7 +37,8 @@ def parse_args():
     ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..5 (3 = ResNet-50-shaped, W=8)")
     ap.add_argument("--sets", type=int, default=2, help="distinct gradient sets cycled through (fresh buffers each step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-steps", type=int, default=3)
+    ap.add_argument("--cpu-seconds", type=float, default=8.0,
+                    help="CPU work per oracle leg (single thread, all cores); whole steps are run until it is used up")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="N",
                     help="also launch the plain copy kernel N times on 1 GiB (byte-counter calibration)")
     ap.add_argument("--pull-copy", action="store_true", help="also time a copying pull of every key (reported apart)")
@@ -68,7 +69,7 @@ def read_traffic(workload: str):
     return None
 
 
-def cpu_baseline(cfg, weights, grads_host, steps: int):
+def cpu_baseline(cfg, weights, grads_host, seconds: float):
     """The oracle as it stands: (i) one thread, (ii) the same function on disjoint
     element ranges from one thread per host core."""
     from oracle import kv_oracle as orc
@@ -79,11 +80,13 @@ def cpu_baseline(cfg, weights, grads_host, steps: int):
         for k, w in enumerate(weights):
             st.set_weights(k, w)
         st.step(grads_host, threads=threads)             # untimed first touch
+        steps = 0
         t0 = time.perf_counter()
-        for _ in range(steps):
+        while steps < 3 or time.perf_counter() - t0 < seconds:
             st.step(grads_host, threads=threads)
+            steps += 1
         dt = (time.perf_counter() - t0) / steps
-        out[label] = (threads, dt)
+        out[label] = (threads, dt, steps)
     return out
 
 
@@ -215,14 +218,15 @@ def main() -> int:
     result.update(extra)
 
     if not args.no_cpu_baseline:
-        base = cpu_baseline(cfg, weights, host_sets[0], args.cpu_steps)
-        threads, dt = base["all"]
+        base = cpu_baseline(cfg, weights, host_sets[0], args.cpu_seconds)
+        threads, dt, cpu_steps = base["all"]
         result["cpu_baseline"] = {
             "value": round(N * cfg.W * itemsize / dt / 1e9, 3),
             "unit": "GB/s",
             "cores": threads,
             "kind": "oracle",
-            "sample": f"{args.cpu_steps} full steps of the same workload (all {K} keys), after one untimed step",
+            "sample": f"{cpu_steps} full steps of the same workload (all {K} keys, one gradient set), after one "
+                      f"untimed step; the single-thread leg ran {base['single'][2]} steps",
             "ms_per_step": round(dt * 1e3, 2),
             "single_thread_value": round(N * cfg.W * itemsize / base["single"][1] / 1e9, 3),
             "single_thread_ms_per_step": round(base["single"][1] * 1e3, 2),

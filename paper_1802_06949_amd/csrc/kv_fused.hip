@@ -54,10 +54,21 @@ template <> struct Grad<true> {
     static __device__ __forceinline__ float widen1(elem e) { return (float)e; }
 };
 
+// Non-temporal mask: bit 0 = gradient loads, bit 1 = loads of w and m, bit 2 = stores of w', m' (and s).
 template <bool NT, typename T>
 __device__ __forceinline__ T load_grad(const T* p) {
     if constexpr (NT) return __builtin_nontemporal_load(p);
     else return *p;
+}
+template <bool NT>
+__device__ __forceinline__ f32x4 load_state(const float* p) {
+    if constexpr (NT) return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+    else return *reinterpret_cast<const f32x4*>(p);
+}
+template <bool NT>
+__device__ __forceinline__ void store_state(float* p, const f32x4& v) {
+    if constexpr (NT) __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(p));
+    else *reinterpret_cast<f32x4*>(p) = v;
 }
 
 // Rank-order left fold: s = g_0; s = s + g_r.  The first term is taken as is.
@@ -214,13 +225,16 @@ __device__ __forceinline__ void scalar_element(const typename Grad<F16>::elem* c
     wp[e] = wn;
 }
 
-template <bool F16, int WT, bool PAIRWISE, bool KEEP, int U, bool NT>
+template <bool F16, int WT, bool PAIRWISE, bool KEEP, int U, int NTM>
 __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
     using G = Grad<F16>;
     using E = typename G::elem;
     constexpr int NV = G::VEC;
     constexpr int Q = NV / 4;                           // float4 pieces of w / m per gradient vector
     constexpr int TILE = KV_THREADS * NV * U;
+    constexpr bool NT = (NTM & 1) != 0;      // gradient loads
+    constexpr bool NTL = (NTM & 2) != 0;     // w, m loads
+    constexpr bool NTS = (NTM & 4) != 0;     // w', m', s stores
     const int W = WT > 0 ? WT : a.W;
     const int tid = threadIdx.x;
 
@@ -258,8 +272,8 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
                 const int64_t e = e0 + (int64_t)(tid + u * KV_THREADS) * NV;
 #pragma unroll
                 for (int q = 0; q < Q; ++q) {
-                    w4[u][q] = *reinterpret_cast<const f32x4*>(wp + e + 4 * q);
-                    m4[u][q] = *reinterpret_cast<const f32x4*>(mp + e + 4 * q);
+                    w4[u][q] = load_state<NTL>(wp + e + 4 * q);
+                    m4[u][q] = load_state<NTL>(mp + e + 4 * q);
                 }
             }
 #pragma unroll
@@ -279,9 +293,9 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
                         sgd_update(s[u][4 * q + c], w4[u][q][c], m4[u][q][c], a.rescale, a.lr, a.momentum, a.wd, wo, mo);
                         wn[c] = wo; mn[c] = mo; sv[c] = s[u][4 * q + c];
                     }
-                    if constexpr (KEEP) *reinterpret_cast<f32x4*>(sp + e + 4 * q) = sv;
-                    *reinterpret_cast<f32x4*>(mp + e + 4 * q) = mn;
-                    *reinterpret_cast<f32x4*>(wp + e + 4 * q) = wn;
+                    if constexpr (KEEP) store_state<NTS>(sp + e + 4 * q, sv);
+                    store_state<NTS>(mp + e + 4 * q, mn);
+                    store_state<NTS>(wp + e + 4 * q, wn);
                 }
             }
         } else if (vec_ok) {
@@ -293,8 +307,8 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
                 reduce_vec<F16, WT, PAIRWISE, NT>(gp, W, e, s);
 #pragma unroll
                 for (int q = 0; q < Q; ++q) {
-                    const f32x4 wv = *reinterpret_cast<const f32x4*>(wp + e + 4 * q);
-                    const f32x4 mv = *reinterpret_cast<const f32x4*>(mp + e + 4 * q);
+                    const f32x4 wv = load_state<NTL>(wp + e + 4 * q);
+                    const f32x4 mv = load_state<NTL>(mp + e + 4 * q);
                     f32x4 wn, mn, sv;
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
@@ -302,9 +316,9 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
                         sgd_update(s[4 * q + c], wv[c], mv[c], a.rescale, a.lr, a.momentum, a.wd, wo, mo);
                         wn[c] = wo; mn[c] = mo; sv[c] = s[4 * q + c];
                     }
-                    if constexpr (KEEP) *reinterpret_cast<f32x4*>(sp + e + 4 * q) = sv;
-                    *reinterpret_cast<f32x4*>(mp + e + 4 * q) = mn;
-                    *reinterpret_cast<f32x4*>(wp + e + 4 * q) = wn;
+                    if constexpr (KEEP) store_state<NTS>(sp + e + 4 * q, sv);
+                    store_state<NTS>(mp + e + 4 * q, mn);
+                    store_state<NTS>(wp + e + 4 * q, wn);
                 }
             }
             const int rem = td.count - nvec * NV;
@@ -316,16 +330,20 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
     }
 }
 
-template <bool F16, int WT, bool PAIRWISE, bool KEEP, int U, bool NT>
+template <bool F16, int WT, bool PAIRWISE, bool KEEP, int U, int NTM>
 hipError_t launch_one(const KvLaunchArgs& a, unsigned grid, hipStream_t st) {
-    hipLaunchKernelGGL((kv_fused<F16, WT, PAIRWISE, KEEP, U, NT>), dim3(grid), dim3(KV_THREADS), 0, st, a);
+    hipLaunchKernelGGL((kv_fused<F16, WT, PAIRWISE, KEEP, U, NTM>), dim3(grid), dim3(KV_THREADS), 0, st, a);
     return hipGetLastError();
 }
 
 template <bool F16, int WT, bool PAIRWISE, bool KEEP, int U>
 hipError_t pick_nt(const KvKernelSel& s, const KvLaunchArgs& a, unsigned grid, hipStream_t st) {
-    return s.nontemporal ? launch_one<F16, WT, PAIRWISE, KEEP, U, true>(a, grid, st)
-                         : launch_one<F16, WT, PAIRWISE, KEEP, U, false>(a, grid, st);
+    switch (s.nontemporal) {
+        case 0: return launch_one<F16, WT, PAIRWISE, KEEP, U, 0>(a, grid, st);
+        case 1: return launch_one<F16, WT, PAIRWISE, KEEP, U, 1>(a, grid, st);
+        case 5: return launch_one<F16, WT, PAIRWISE, KEEP, U, 5>(a, grid, st);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 template <bool F16, int WT, bool PAIRWISE, bool KEEP>

@@ -413,19 +413,22 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     st->rescale = params->rescale > 0.0f ? params->rescale : 1.0f / (float)W;
     st->stream = static_cast<hipStream_t>(hip_stream);
 
-    // defaults: two vectors per lane up to W = 8, one above
-    st->unroll = W <= 8 ? 2 : 1;
+    // Defaults from sweeps on MI355X: one 16-byte vector per lane and rank, one workgroup
+    // per tile, non-temporal gradient loads (they keep the streamed gradients from evicting
+    // w and m out of the memory-side cache), contiguous tile ranges per XCD for fp32.
+    st->unroll = 1;
     st->wg_per_cu = 0;
     st->nontemporal = 1;
-    st->xcd_remap = 0;
+    st->xcd_remap = grad_dtype == KV_F16 ? 0 : 1;
     if (tuning) {
         if (tuning->unroll != 0) st->unroll = tuning->unroll;
         if (tuning->workgroups_per_cu >= 0) st->wg_per_cu = tuning->workgroups_per_cu;
-        if (tuning->nontemporal >= 0) st->nontemporal = tuning->nontemporal ? 1 : 0;
+        if (tuning->nontemporal >= 0) st->nontemporal = tuning->nontemporal;
         if (tuning->xcd_remap >= 0) st->xcd_remap = tuning->xcd_remap ? 1 : 0;
     }
-    if (st->unroll != 1 && st->unroll != 2 && st->unroll != 4) {
-        set_err(g_err, "kv_init: tuning.unroll must be 1, 2 or 4");
+    const int nt = st->nontemporal;
+    if ((st->unroll != 1 && st->unroll != 2 && st->unroll != 4) || !(nt == 0 || nt == 1 || nt == 5)) {
+        set_err(g_err, "kv_init: tuning.unroll must be 1, 2 or 4 and tuning.nontemporal one of 0, 1, 5");
         delete st;
         return KV_ERR_ARG;
     }
