@@ -84,9 +84,9 @@ typedef struct kv_sgd_params {
  *   unroll            16-byte vectors per thread per rank in one tile: 1, 2 or 4 (0 = default)
  *   workgroups_per_cu cap of resident workgroups per compute unit for the grid-stride
  *                     loop over tiles; 0 = one workgroup per tile
- *   nontemporal       bit mask of accesses that carry the non-temporal hint: 1 = gradient loads,
- *                     4 = stores of w', m' (and s); one of 0, 1, 5;
- *                     -1 = default
+ *   nontemporal       cache policy: bit 0 = gradient loads carry the non-temporal hint; plus the policy
+ *                     of the stores of w', m' (and s): 0 = plain, 4 = non-temporal, 8 = write through L2;
+ *                     one of 0, 1, 5, 9; -1 = default
  *   xcd_remap         1 = tiles are dealt to the 8 XCDs in contiguous ranges, 0 = round robin,
  *                     -1 = default
  */

@@ -7,21 +7,16 @@ constexpr int KV_THREADS = 256;          // 4 wavefronts of 64 lanes per workgro
 // One tile: a contiguous piece of one key handled by one workgroup pass.
 // Element counts; seg_off is a multiple of the tile size, so 16-byte vectors of
 // the arena and of 16-byte-aligned gradient buffers line up.
-struct alignas(16) KvTile {
-    int32_t seg;       // segment (key) index in launch order
-    int32_t count;     // elements in this tile (<= tile size; the last tile of a key may be ragged)
-    int64_t seg_off;   // first element of the tile inside the key
-};
-
-// One segment = one key as laid out in the arenas.
-struct alignas(16) KvSeg {
-    int64_t arena_off; // first element of the key in the w / m / s arenas (multiple of 4)
-    int64_t numel;
+struct alignas(32) KvTile {
+    int32_t seg;        // segment (key) index in launch order: row of the gradient-pointer table
+    int32_t count;      // elements in this tile (<= tile size; the last tile of a key may be ragged)
+    int64_t arena_off;  // first element of the tile in the w / m / s arenas (multiple of 4)
+    int64_t seg_off;    // first element of the tile inside the key
+    int64_t reserved;
 };
 
 struct KvLaunchArgs {
     const KvTile* tiles;          // device, all tiles of the store in (unit, key, offset) order
-    const KvSeg* segs;            // device, all segments in (unit, key) order
     const void* const* gptrs;     // device, [num_segs * W] gradient pointers, segment-major
     float* w;                     // weight arena
     float* m;                     // momentum arena

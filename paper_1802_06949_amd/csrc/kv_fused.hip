@@ -54,7 +54,10 @@ template <> struct Grad<true> {
     static __device__ __forceinline__ float widen1(elem e) { return (float)e; }
 };
 
-// Non-temporal mask: bit 0 = gradient loads, bit 1 = loads of w and m, bit 2 = stores of w', m' (and s).
+// Cache-policy mask of a kernel instantiation:
+//   bit 0       gradient loads carry the non-temporal hint
+//   bit 1       loads of w and m carry it
+//   bits 2..3   stores of w', m' (and s): 0 = plain, 4 = non-temporal, 8 = agent scope (write through L2)
 template <bool NT, typename T>
 __device__ __forceinline__ T load_grad(const T* p) {
     if constexpr (NT) return __builtin_nontemporal_load(p);
@@ -65,10 +68,21 @@ __device__ __forceinline__ f32x4 load_state(const float* p) {
     if constexpr (NT) return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
     else return *reinterpret_cast<const f32x4*>(p);
 }
-template <bool NT>
-__device__ __forceinline__ void store_state(float* p, const f32x4& v) {
-    if constexpr (NT) __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(p));
-    else *reinterpret_cast<f32x4*>(p) = v;
+// Stores 16 bytes at element `k` of the uniform base pointer `base`.  Policy 8 uses a raw
+// buffer store, whose cache-policy operand can carry the sc1 bit (write through L2 to memory
+// at once instead of leaving a dirty line in L2); the buffer descriptor spans exactly the
+// bytes handed in, so an out-of-range lane could not write.
+template <int POL>
+__device__ __forceinline__ void store_state(float* base, int k, unsigned span_bytes, const f32x4& v) {
+    if constexpr (POL == 4) {
+        __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(base + k));
+    } else if constexpr (POL == 8) {
+        typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(base, 0, span_bytes, 0x00020000);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rsrc, k * 4, 0, /*sc1*/ 16);
+    } else {
+        *reinterpret_cast<f32x4*>(base + k) = v;
+    }
 }
 
 // Rank-order left fold: s = g_0; s = s + g_r.  The first term is taken as is.
@@ -143,10 +157,18 @@ template <int NV> struct FoldPair {
 template <int NV, bool PAIRWISE> struct FoldSel { using type = FoldSeq<NV>; };
 template <int NV> struct FoldSel<NV, true> { using type = FoldPair<NV>; };
 
-// Sum over ranks of the 16-byte vector that starts at element `eoff` of the key.
+// The tile table and the gradient-pointer table are written by the host before the
+// launch and never by a kernel, so they are read through the constant address
+// space: uniform addresses become scalar loads (s_load) instead of vector loads plus
+// readfirstlane.  Gradient buffers are read through the global address space
+// (global_load, not flat_load).
+#define KV_CONST __attribute__((address_space(4)))
+#define KV_GLOBAL __attribute__((address_space(1)))
+
+// Sum over ranks of the 16-byte vector that starts `boff` bytes into every rank's copy of the key.
 template <bool F16, int WT, bool PAIRWISE, bool NT>
-__device__ __forceinline__ void reduce_vec(const typename Grad<F16>::elem* const* __restrict__ gp, int W,
-                                           int64_t eoff, float (&s)[Grad<F16>::VEC]) {
+__device__ __forceinline__ void reduce_vec(const uint64_t KV_CONST* gp, int W, int64_t boff,
+                                           float (&s)[Grad<F16>::VEC]) {
     using G = Grad<F16>;
     using V = typename G::vec;
     constexpr int NV = G::VEC;
@@ -157,7 +179,7 @@ __device__ __forceinline__ void reduce_vec(const typename Grad<F16>::elem* const
         for (int r0 = 0; r0 < WT; r0 += CH) {
             V g[CH];
 #pragma unroll
-            for (int j = 0; j < CH; ++j) g[j] = load_grad<NT>(reinterpret_cast<const V*>(gp[r0 + j] + eoff));
+            for (int j = 0; j < CH; ++j) g[j] = load_grad<NT>((const V KV_GLOBAL*)(gp[r0 + j] + (uint64_t)boff));
 #pragma unroll
             for (int j = 0; j < CH; ++j) {
                 float t[NV];
@@ -170,7 +192,7 @@ __device__ __forceinline__ void reduce_vec(const typename Grad<F16>::elem* const
             V g[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if (r0 + j < W) g[j] = load_grad<NT>(reinterpret_cast<const V*>(gp[r0 + j] + eoff));
+                if (r0 + j < W) g[j] = load_grad<NT>((const V KV_GLOBAL*)(gp[r0 + j] + (uint64_t)boff));
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 if (r0 + j < W) {
@@ -184,15 +206,16 @@ __device__ __forceinline__ void reduce_vec(const typename Grad<F16>::elem* const
     f.finish(s);
 }
 
-// Same for a single element (ragged tails and gradient buffers that are not
-// 16-byte aligned).
+// Same for the single element `e` of the key (ragged tails and gradient buffers
+// that are not 16-byte aligned).
 template <bool F16, int WT, bool PAIRWISE>
-__device__ __forceinline__ float reduce_one(const typename Grad<F16>::elem* const* __restrict__ gp, int W, int64_t e) {
+__device__ __forceinline__ float reduce_one(const uint64_t KV_CONST* gp, int W, int64_t e) {
     using G = Grad<F16>;
+    using E = typename G::elem;
     typename FoldSel<1, PAIRWISE>::type f;
     const int n = WT > 0 ? WT : W;
     for (int r = 0; r < n; ++r) {
-        float t[1] = {G::widen1(gp[r][e])};
+        float t[1] = {G::widen1(((const E KV_GLOBAL*)gp[r])[e])};
         f.push(t);
     }
     float o[1];
@@ -213,16 +236,33 @@ __device__ __forceinline__ void sgd_update(float s, float w, float m, float resc
     w_new = w + dw;
 }
 
+// Element `k` of the tile: e = element index inside the key, wp/mp/sp point at the tile start.
 template <bool F16, int WT, bool PAIRWISE, bool KEEP>
-__device__ __forceinline__ void scalar_element(const typename Grad<F16>::elem* const* __restrict__ gp, int W, int64_t e,
+__device__ __forceinline__ void scalar_element(const uint64_t KV_CONST* gp, int W, int64_t e, int k,
                                                float* __restrict__ wp, float* __restrict__ mp, float* __restrict__ sp,
                                                const KvLaunchArgs& a) {
     const float s = reduce_one<F16, WT, PAIRWISE>(gp, W, e);
     float wn, mn;
-    sgd_update(s, wp[e], mp[e], a.rescale, a.lr, a.momentum, a.wd, wn, mn);
-    if constexpr (KEEP) sp[e] = s;
-    mp[e] = mn;
-    wp[e] = wn;
+    sgd_update(s, wp[k], mp[k], a.rescale, a.lr, a.momentum, a.wd, wn, mn);
+    if constexpr (KEEP) sp[k] = s;
+    mp[k] = mn;
+    wp[k] = wn;
+}
+
+// Updates the four elements k..k+3 of the tile whose arenas start at wp / mp / sp.
+template <bool KEEP, int NTS>
+__device__ __forceinline__ void update_store4(const float* s4, const f32x4& wv, const f32x4& mv, float* wp, float* mp,
+                                              float* sp, int k, unsigned span_bytes, const KvLaunchArgs& a) {
+    f32x4 wn, mn, sv;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        float wo, mo;
+        sgd_update(s4[c], wv[c], mv[c], a.rescale, a.lr, a.momentum, a.wd, wo, mo);
+        wn[c] = wo; mn[c] = mo; sv[c] = s4[c];
+    }
+    if constexpr (KEEP) store_state<NTS>(sp, k, span_bytes, sv);
+    store_state<NTS>(mp, k, span_bytes, mn);
+    store_state<NTS>(wp, k, span_bytes, wn);
 }
 
 template <bool F16, int WT, bool PAIRWISE, bool KEEP, int U, int NTM>
@@ -230,13 +270,18 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
     using G = Grad<F16>;
     using E = typename G::elem;
     constexpr int NV = G::VEC;
-    constexpr int Q = NV / 4;                           // float4 pieces of w / m per gradient vector
+    constexpr int Q = NV / 4;                // float4 pieces of w / m per gradient vector
     constexpr int TILE = KV_THREADS * NV * U;
     constexpr bool NT = (NTM & 1) != 0;      // gradient loads
     constexpr bool NTL = (NTM & 2) != 0;     // w, m loads
-    constexpr bool NTS = (NTM & 4) != 0;     // w', m', s stores
+    constexpr int NTS = NTM & 12;            // store policy of w', m', s
     const int W = WT > 0 ? WT : a.W;
     const int tid = threadIdx.x;
+
+    // a KvTile as four 64-bit words: {seg | count << 32, arena_off, seg_off, reserved}
+    static_assert(sizeof(KvTile) == 32, "tile layout");
+    const int64_t KV_CONST* tiles = (const int64_t KV_CONST*)a.tiles + a.tile_lo * 4;
+    const uint64_t KV_CONST* table = (const uint64_t KV_CONST*)a.gptrs;
 
     const int64_t ntiles = a.tile_hi - a.tile_lo;
     // With xcd_remap, consecutive workgroup ids (which the hardware deals round-robin
@@ -250,82 +295,79 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
             t = (i & 7) * chunk + (i >> 3);
             if (t >= ntiles) continue;
         }
-        const KvTile td = a.tiles[a.tile_lo + t];
-        const KvSeg sd = a.segs[td.seg];
-        const E* const* __restrict__ gp = reinterpret_cast<const E* const*>(a.gptrs) + (int64_t)td.seg * W;
+        struct { int32_t seg, count; int64_t arena_off, seg_off; } td;
+        {
+            const int64_t KV_CONST* tw = tiles + t * 4;
+            const int64_t w0 = tw[0];
+            td.seg = (int32_t)(w0 & 0xFFFFFFFF);
+            td.count = (int32_t)(w0 >> 32);
+            td.arena_off = tw[1];
+            td.seg_off = tw[2];
+        }
+        float* __restrict__ wp = a.w + td.arena_off;
+        float* __restrict__ mp = a.m + td.arena_off;
+        float* __restrict__ sp = KEEP ? a.s + td.arena_off : nullptr;
+        const uint64_t KV_CONST* gp = table + (int64_t)td.seg * W;
+        const bool full = td.count == TILE;
+        const unsigned span_bytes = (unsigned)td.count * 4u;      // bytes of this tile in each arena
 
-        uintptr_t bits = 0;
-        for (int r = 0; r < W; ++r) bits |= reinterpret_cast<uintptr_t>(gp[r]);
+        // A full tile lies wholly inside the arena, so its w and m vectors can be requested
+        // before the gradient pointers have arrived (they are dropped in the rare case that
+        // the gradient buffers turn out not to be 16-byte aligned).
+        f32x4 w4[U][Q], m4[U][Q];
+        if (full) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int k = (tid + u * KV_THREADS) * NV;
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    w4[u][q] = load_state<NTL>(wp + k + 4 * q);
+                    m4[u][q] = load_state<NTL>(mp + k + 4 * q);
+                }
+            }
+        }
+
+        uint64_t bits = 0;
+        for (int r = 0; r < W; ++r) bits |= gp[r];
         const bool vec_ok = (bits & 15u) == 0;
 
-        const int64_t e0 = td.seg_off;
-        float* __restrict__ wp = a.w + sd.arena_off;
-        float* __restrict__ mp = a.m + sd.arena_off;
-        float* __restrict__ sp = KEEP ? a.s + sd.arena_off : nullptr;
-
-        if (vec_ok && td.count == TILE) {
-            // full tile: issue every load of every unrolled vector before the first store
-            f32x4 w4[U][Q], m4[U][Q];
+        if (vec_ok && full) {
+            // every gradient load of every unrolled vector is issued before the first store
             float s[U][NV];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t e = e0 + (int64_t)(tid + u * KV_THREADS) * NV;
-#pragma unroll
-                for (int q = 0; q < Q; ++q) {
-                    w4[u][q] = load_state<NTL>(wp + e + 4 * q);
-                    m4[u][q] = load_state<NTL>(mp + e + 4 * q);
-                }
+                const int64_t e = td.seg_off + (int64_t)(tid + u * KV_THREADS) * NV;
+                reduce_vec<F16, WT, PAIRWISE, NT>(gp, W, e * (int64_t)sizeof(E), s[u]);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t e = e0 + (int64_t)(tid + u * KV_THREADS) * NV;
-                reduce_vec<F16, WT, PAIRWISE, NT>(gp, W, e, s[u]);
-            }
+                const int k = (tid + u * KV_THREADS) * NV;
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int64_t e = e0 + (int64_t)(tid + u * KV_THREADS) * NV;
-#pragma unroll
-                for (int q = 0; q < Q; ++q) {
-                    f32x4 wn, mn, sv;
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        float wo, mo;
-                        sgd_update(s[u][4 * q + c], w4[u][q][c], m4[u][q][c], a.rescale, a.lr, a.momentum, a.wd, wo, mo);
-                        wn[c] = wo; mn[c] = mo; sv[c] = s[u][4 * q + c];
-                    }
-                    if constexpr (KEEP) store_state<NTS>(sp + e + 4 * q, sv);
-                    store_state<NTS>(mp + e + 4 * q, mn);
-                    store_state<NTS>(wp + e + 4 * q, wn);
-                }
+                for (int q = 0; q < Q; ++q)
+                    update_store4<KEEP, NTS>(&s[u][4 * q], w4[u][q], m4[u][q], wp, mp, sp, k + 4 * q, span_bytes, a);
             }
         } else if (vec_ok) {
             // ragged tile: whole vectors first, then at most NV-1 single elements
             const int nvec = td.count / NV;
             for (int v = tid; v < nvec; v += KV_THREADS) {
-                const int64_t e = e0 + (int64_t)v * NV;
+                const int k = v * NV;
                 float s[NV];
-                reduce_vec<F16, WT, PAIRWISE, NT>(gp, W, e, s);
+                reduce_vec<F16, WT, PAIRWISE, NT>(gp, W, (td.seg_off + k) * (int64_t)sizeof(E), s);
 #pragma unroll
                 for (int q = 0; q < Q; ++q) {
-                    const f32x4 wv = load_state<NTL>(wp + e + 4 * q);
-                    const f32x4 mv = load_state<NTL>(mp + e + 4 * q);
-                    f32x4 wn, mn, sv;
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        float wo, mo;
-                        sgd_update(s[4 * q + c], wv[c], mv[c], a.rescale, a.lr, a.momentum, a.wd, wo, mo);
-                        wn[c] = wo; mn[c] = mo; sv[c] = s[4 * q + c];
-                    }
-                    if constexpr (KEEP) store_state<NTS>(sp + e + 4 * q, sv);
-                    store_state<NTS>(mp + e + 4 * q, mn);
-                    store_state<NTS>(wp + e + 4 * q, wn);
+                    const f32x4 wv = load_state<NTL>(wp + k + 4 * q);
+                    const f32x4 mv = load_state<NTL>(mp + k + 4 * q);
+                    update_store4<KEEP, NTS>(&s[4 * q], wv, mv, wp, mp, sp, k + 4 * q, span_bytes, a);
                 }
             }
             const int rem = td.count - nvec * NV;
-            if (tid < rem) scalar_element<F16, WT, PAIRWISE, KEEP>(gp, W, e0 + (int64_t)nvec * NV + tid, wp, mp, sp, a);
+            if (tid < rem) {
+                const int k = nvec * NV + tid;
+                scalar_element<F16, WT, PAIRWISE, KEEP>(gp, W, td.seg_off + k, k, wp, mp, sp, a);
+            }
         } else {
             for (int k = tid; k < td.count; k += KV_THREADS)
-                scalar_element<F16, WT, PAIRWISE, KEEP>(gp, W, e0 + k, wp, mp, sp, a);
+                scalar_element<F16, WT, PAIRWISE, KEEP>(gp, W, td.seg_off + k, k, wp, mp, sp, a);
         }
     }
 }
@@ -342,6 +384,7 @@ hipError_t pick_nt(const KvKernelSel& s, const KvLaunchArgs& a, unsigned grid, h
         case 0: return launch_one<F16, WT, PAIRWISE, KEEP, U, 0>(a, grid, st);
         case 1: return launch_one<F16, WT, PAIRWISE, KEEP, U, 1>(a, grid, st);
         case 5: return launch_one<F16, WT, PAIRWISE, KEEP, U, 5>(a, grid, st);
+        case 9: return launch_one<F16, WT, PAIRWISE, KEEP, U, 9>(a, grid, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -67,25 +67,21 @@ int kv_plan_build(kv_plan& plan, int num_keys, const int64_t* key_numel, int gra
     return KV_OK;
 }
 
-void kv_plan_tiles(const kv_plan& plan, int tile_elems, std::vector<KvTile>& tiles, std::vector<KvSeg>& segs,
+void kv_plan_tiles(const kv_plan& plan, int tile_elems, std::vector<KvTile>& tiles,
                    std::vector<int64_t>& unit_tile_begin) {
     tiles.clear();
-    segs.clear();
     unit_tile_begin.clear();
     for (const auto& u : plan.units) {
         unit_tile_begin.push_back((int64_t)tiles.size());
         for (int k : u.keys) {
-            const int seg = (int)segs.size();
-            KvSeg sd;
-            sd.arena_off = plan.key_arena_off[k];
-            sd.numel = plan.numel[k];
-            segs.push_back(sd);
             for (int64_t off = 0; off < plan.numel[k]; off += tile_elems) {
                 KvTile t;
-                t.seg = seg;
+                t.seg = plan.key_seg[k];
                 const int64_t left = plan.numel[k] - off;
                 t.count = (int32_t)(left < tile_elems ? left : tile_elems);
+                t.arena_off = plan.key_arena_off[k] + off;
                 t.seg_off = off;
+                t.reserved = 0;
                 tiles.push_back(t);
             }
         }

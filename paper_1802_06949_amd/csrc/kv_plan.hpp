@@ -33,7 +33,7 @@ int kv_plan_build(kv_plan& plan, int num_keys, const int64_t* key_numel, int gra
 
 // Cuts every key into tiles of tile_elems elements (the last one ragged), in
 // (unit, key, offset) order.  unit_tile_begin gets num_units + 1 entries.
-void kv_plan_tiles(const kv_plan& plan, int tile_elems, std::vector<KvTile>& tiles, std::vector<KvSeg>& segs,
+void kv_plan_tiles(const kv_plan& plan, int tile_elems, std::vector<KvTile>& tiles,
                    std::vector<int64_t>& unit_tile_begin);
 
 struct kv_chain {

@@ -62,7 +62,6 @@ struct kv_store {
     float* m = nullptr;
     float* s = nullptr;
     KvTile* d_tiles = nullptr;
-    KvSeg* d_segs = nullptr;
     std::vector<int64_t> unit_tile_begin;
 
     size_t table_elems = 0;                       // num_segs * W
@@ -107,7 +106,6 @@ void free_store(kv_store* st) {
     if (st->m) (void)hipFree(st->m);
     if (st->s) (void)hipFree(st->s);
     if (st->d_tiles) (void)hipFree(st->d_tiles);
-    if (st->d_segs) (void)hipFree(st->d_segs);
     for (int i = 0; i < NSLOT; ++i)
         if (st->d_slot[i]) (void)hipFree(st->d_slot[i]);
     if (st->h_stage) (void)hipHostFree(st->h_stage);
@@ -190,7 +188,6 @@ int launch_run(kv_store* st, int first, int n) {
         if (rc != KV_OK) return rc;
         KvLaunchArgs a{};
         a.tiles = st->d_tiles;
-        a.segs = st->d_segs;
         a.gptrs = table;
         a.w = st->w;
         a.m = st->m;
@@ -413,13 +410,14 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     st->rescale = params->rescale > 0.0f ? params->rescale : 1.0f / (float)W;
     st->stream = static_cast<hipStream_t>(hip_stream);
 
-    // Defaults from sweeps on MI355X: one 16-byte vector per lane and rank, one workgroup
-    // per tile, non-temporal gradient loads (they keep the streamed gradients from evicting
-    // w and m out of the memory-side cache), contiguous tile ranges per XCD for fp32.
+    // Defaults from sweeps on MI355X.  Non-temporal gradient loads keep the streamed gradients
+    // from evicting w and m out of the memory-side cache; contiguous tile ranges per XCD and
+    // (for fp32 gradients) write-through stores of w', m' are worth a few percent each.
+    const bool f16 = grad_dtype == KV_F16;
     st->unroll = 1;
     st->wg_per_cu = 0;
-    st->nontemporal = 1;
-    st->xcd_remap = grad_dtype == KV_F16 ? 0 : 1;
+    st->nontemporal = f16 ? 1 : 9;
+    st->xcd_remap = 1;
     if (tuning) {
         if (tuning->unroll != 0) st->unroll = tuning->unroll;
         if (tuning->workgroups_per_cu >= 0) st->wg_per_cu = tuning->workgroups_per_cu;
@@ -427,8 +425,8 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
         if (tuning->xcd_remap >= 0) st->xcd_remap = tuning->xcd_remap ? 1 : 0;
     }
     const int nt = st->nontemporal;
-    if ((st->unroll != 1 && st->unroll != 2 && st->unroll != 4) || !(nt == 0 || nt == 1 || nt == 5)) {
-        set_err(g_err, "kv_init: tuning.unroll must be 1, 2 or 4 and tuning.nontemporal one of 0, 1, 5");
+    if ((st->unroll != 1 && st->unroll != 2 && st->unroll != 4) || !(nt == 0 || nt == 1 || nt == 5 || nt == 9)) {
+        set_err(g_err, "kv_init: tuning.unroll must be 1, 2 or 4 and tuning.nontemporal one of 0, 1, 5, 9");
         delete st;
         return KV_ERR_ARG;
     }
@@ -450,14 +448,13 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     if (cus > 0) st->num_cus = cus;
 
     std::vector<KvTile> tiles;
-    std::vector<KvSeg> segs;
     try {
-        kv_plan_tiles(st->plan, st->tile_elems, tiles, segs, st->unit_tile_begin);
-        st->table_elems = segs.size() * (size_t)W;
+        kv_plan_tiles(st->plan, st->tile_elems, tiles, st->unit_tile_begin);
+        st->table_elems = st->plan.seg_key.size() * (size_t)W;
         st->cur_ptrs.assign(st->table_elems, nullptr);
         for (int i = 0; i < NSLOT; ++i) {
             st->mirror[i].assign(st->table_elems, nullptr);
-            st->row_valid[i].assign(segs.size(), 0);
+            st->row_valid[i].assign(st->plan.seg_key.size(), 0);
         }
         st->deferred.resize(st->plan.units.size());
         st->log.reserve(64);
@@ -477,18 +474,15 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
         KV_INIT_HIP(hipMemsetAsync(st->s, 0, arena_bytes, st->stream));
     }
     const size_t tile_bytes = (tiles.empty() ? 1 : tiles.size()) * sizeof(KvTile);
-    const size_t seg_bytes = segs.size() * sizeof(KvSeg);
     KV_INIT_HIP(hipMalloc((void**)&st->d_tiles, tile_bytes));
-    KV_INIT_HIP(hipMalloc((void**)&st->d_segs, seg_bytes));
     if (!tiles.empty())
         KV_INIT_HIP(hipMemcpyAsync(st->d_tiles, tiles.data(), tiles.size() * sizeof(KvTile), hipMemcpyHostToDevice, st->stream));
-    KV_INIT_HIP(hipMemcpyAsync(st->d_segs, segs.data(), seg_bytes, hipMemcpyHostToDevice, st->stream));
     for (int i = 0; i < NSLOT; ++i) KV_INIT_HIP(hipMalloc((void**)&st->d_slot[i], st->table_elems * sizeof(void*)));
     KV_INIT_HIP(hipHostMalloc((void**)&st->h_stage, (size_t)NSTAGE * st->table_elems * sizeof(void*), hipHostMallocDefault));
     for (int i = 0; i < NSTAGE; ++i) KV_INIT_HIP(hipEventCreateWithFlags(&st->stage_ev[i], hipEventDisableTiming));
     KV_INIT_HIP(hipEventCreate(&st->t0));
     KV_INIT_HIP(hipEventCreate(&st->t1));
-    // the host vectors `tiles` and `segs` die at return: wait for their uploads
+    // the host vector `tiles` dies at return: wait for its upload
     KV_INIT_HIP(hipStreamSynchronize(st->stream));
 #undef KV_INIT_HIP
     *out = st;
