@@ -42,6 +42,10 @@ def parse_args():
     ap.add_argument("--calib-copy", type=int, default=0, metavar="N",
                     help="also launch the plain copy kernel N times on 1 GiB (byte-counter calibration)")
     ap.add_argument("--pull-copy", action="store_true", help="also time a copying pull of every key (reported apart)")
+    ap.add_argument("--schedule", choices=["chained", "funnel", "concurrent"], default="chained",
+                    help="chained = one merged launch per step (headline); funnel / concurrent = one launch per key")
+    ap.add_argument("--streams", type=int, default=4, help="concurrent schedule: number of streams")
+    ap.add_argument("--outstanding", type=int, default=0, help="concurrent schedule: barrier after this many keys")
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--workgroups-per-cu", type=int, default=-1)
     ap.add_argument("--nontemporal", type=int, default=-1)
@@ -134,6 +138,8 @@ def main() -> int:
         if w.size:
             store.set_weights(k, torch.from_numpy(w).cuda())
     store.wait()
+    sched = {"chained": kv.KV_SCHED_CHAINED, "funnel": kv.KV_SCHED_FUNNEL, "concurrent": kv.KV_SCHED_CONCURRENT}[args.schedule]
+    store.set_schedule(sched, args.streams, args.outstanding)
     keys = list(range(K))
     lists = [store.make_push_list(keys, d) for d in dev_sets]
 
@@ -197,6 +203,8 @@ def main() -> int:
             "gradient_sets_cycled": nsets,
             "units": store.plan.num_units,
             "launches_per_step": launches_per_step,
+            "schedule": args.schedule + (f" ({args.streams} streams, barrier every {args.outstanding} keys)"
+                                         if args.schedule == "concurrent" else ""),
             "pull": "zero-copy (weights read in place in the arena)",
         },
         "params_per_s": round(N / t_step, 1),

@@ -63,7 +63,24 @@ enum kv_reduce_order { KV_REDUCE_SEQUENTIAL = 0,          /* s = g_0; s += g_r, 
                        KV_REDUCE_PAIRWISE   = 1 };        /* balanced tree, see below */
 enum kv_flags { KV_FLAG_KEEP_SUM = 1u };                  /* also store s (kv_pull_grad) */
 
+/*
+ * The paper's three ways of embedding the aggregation into the worker's task flow
+ * (section "Embedding MPI operators in DAGs").  All three compute the same values.
+ *   KV_SCHED_CHAINED     "MPI Dependency Chaining": pushes only record; units are launched in one
+ *                        fixed order, merged, without ever blocking the issuing thread.  Default.
+ *   KV_SCHED_FUNNEL      "MPI Funneled": the issuing thread does the aggregation of a key itself, in
+ *                        its push, and nothing else starts before it is done: one key per launch,
+ *                        no buckets (the paper keeps one communication buffer per key), the host
+ *                        blocks until the launch has completed, so one aggregation is outstanding.
+ *   KV_SCHED_CONCURRENT  "MPI Concurrent Communications": several communicators, here HIP streams;
+ *                        a key is hashed to stream (key mod n_streams) and launched there by its
+ *                        push without blocking; after every `outstanding` pushes (0 = never) the
+ *                        store runs kv_barrier, as the paper's Python loop does every OUTSTANDING keys.
+ */
+enum kv_schedule { KV_SCHED_CHAINED = 0, KV_SCHED_FUNNEL = 1, KV_SCHED_CONCURRENT = 2 };
+
 #define KV_MAX_W 256
+#define KV_MAX_STREAMS 64
 
 /*
  * Optimizer parameters.  rescale <= 0 selects 1.0f / (float)W, computed once in
@@ -195,6 +212,20 @@ int kv_weights_ptr(kv_store* store, int key, void** dev_ptr_out);
  * returns KV_ERR_INCOMPLETE if an iteration is only partly pushed or launched.
  */
 int kv_wait(kv_store* store, int key);
+
+/*
+ * kv_set_schedule: the paper's KVStore.create("type").  Allowed only between iterations
+ * (KV_ERR_STATE while pushed keys wait); drains all streams first.  n_streams (1..KV_MAX_STREAMS)
+ * and outstanding (>= 0) are read for KV_SCHED_CONCURRENT only; the extra streams are created by
+ * the store at default priority.  In the concurrent schedule a key's launch, its pulls and its
+ * sets run on the key's stream, ordered after everything issued earlier on the stream given to
+ * kv_init; work the caller issues afterwards on that stream is ordered after a key only through
+ * kv_wait(key) or kv_barrier.  In the launch log per-key launches appear as (key, 0).
+ * kv_barrier: the paper's Kvstore.barrier: blocks until nothing launched so far is outstanding
+ * on any stream.  Unlike kv_wait(-1) it does not report an incomplete iteration.
+ */
+int kv_set_schedule(kv_store* store, int schedule, int n_streams, int outstanding);
+int kv_barrier(kv_store* store);
 
 /* ------------------------------------------------------------------ introspection
  * The plan in use (owned by the store). */

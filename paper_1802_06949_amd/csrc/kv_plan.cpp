@@ -68,12 +68,14 @@ int kv_plan_build(kv_plan& plan, int num_keys, const int64_t* key_numel, int gra
 }
 
 void kv_plan_tiles(const kv_plan& plan, int tile_elems, std::vector<KvTile>& tiles,
-                   std::vector<int64_t>& unit_tile_begin) {
+                   std::vector<int64_t>& unit_tile_begin, std::vector<int64_t>& seg_tile_begin) {
     tiles.clear();
     unit_tile_begin.clear();
+    seg_tile_begin.clear();
     for (const auto& u : plan.units) {
         unit_tile_begin.push_back((int64_t)tiles.size());
         for (int k : u.keys) {
+            seg_tile_begin.push_back((int64_t)tiles.size());         // segments are numbered in this order
             for (int64_t off = 0; off < plan.numel[k]; off += tile_elems) {
                 KvTile t;
                 t.seg = plan.key_seg[k];
@@ -87,6 +89,7 @@ void kv_plan_tiles(const kv_plan& plan, int tile_elems, std::vector<KvTile>& til
         }
     }
     unit_tile_begin.push_back((int64_t)tiles.size());
+    seg_tile_begin.push_back((int64_t)tiles.size());
 }
 
 void kv_chain::reset(const kv_plan* p) {

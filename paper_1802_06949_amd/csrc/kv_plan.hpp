@@ -32,9 +32,10 @@ struct kv_plan {
 int kv_plan_build(kv_plan& plan, int num_keys, const int64_t* key_numel, int grad_dtype, size_t bucket_bytes);
 
 // Cuts every key into tiles of tile_elems elements (the last one ragged), in
-// (unit, key, offset) order.  unit_tile_begin gets num_units + 1 entries.
+// (unit, key, offset) order.  unit_tile_begin gets num_units + 1 entries,
+// seg_tile_begin num_segments + 1.
 void kv_plan_tiles(const kv_plan& plan, int tile_elems, std::vector<KvTile>& tiles,
-                   std::vector<int64_t>& unit_tile_begin);
+                   std::vector<int64_t>& unit_tile_begin, std::vector<int64_t>& seg_tile_begin);
 
 struct kv_chain {
     const kv_plan* plan = nullptr;

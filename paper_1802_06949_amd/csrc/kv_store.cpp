@@ -79,6 +79,17 @@ struct kv_store {
 
     std::vector<std::vector<Deferred>> deferred;  // per unit
 
+    // schedules other than the chained one launch one key at a time
+    int schedule = KV_SCHED_CHAINED;
+    int outstanding = 0;                          // concurrent schedule: barrier after this many pushes (0 = never)
+    int since_barrier = 0;
+    std::vector<hipStream_t> lanes;               // concurrent schedule: one stream per "communicator"
+    hipEvent_t fork_ev = nullptr;                 // orders a lane after the work already on the main stream
+    bool in_list = false;                         // inside kv_push_list: one fork event serves the whole list
+    bool list_forked = false;
+    std::vector<uint8_t> lane_waited;             // per lane: already waits for this list's fork event
+    std::vector<int64_t> seg_tile_begin;          // tiles of segment sgm: [seg_tile_begin[sgm], seg_tile_begin[sgm + 1])
+
     std::vector<std::pair<int, int>> log;
     int64_t launches_total = 0;
 
@@ -111,6 +122,8 @@ void free_store(kv_store* st) {
     if (st->h_stage) (void)hipHostFree(st->h_stage);
     for (int i = 0; i < NSTAGE; ++i)
         if (st->stage_ev[i]) (void)hipEventDestroy(st->stage_ev[i]);
+    for (hipStream_t l : st->lanes) (void)hipStreamDestroy(l);
+    if (st->fork_ev) (void)hipEventDestroy(st->fork_ev);
     if (st->t0) (void)hipEventDestroy(st->t0);
     if (st->t1) (void)hipEventDestroy(st->t1);
     delete st;
@@ -126,7 +139,7 @@ int check_key(kv_store* st, int key) {
 
 // Device table that holds the current pointers of segments [s0, s1); uploads them if
 // no cached table matches.
-int table_for(kv_store* st, int s0, int s1, const void* const** table_out) {
+int table_for(kv_store* st, int s0, int s1, hipStream_t stream, const void* const** table_out) {
     const size_t W = (size_t)st->W;
     const size_t lo = (size_t)s0 * W, n = (size_t)(s1 - s0) * W;
     for (int k = 0; k < NSLOT; ++k) {
@@ -157,8 +170,8 @@ int table_for(kv_store* st, int s0, int s1, const void* const** table_out) {
     }
     const void** stage = st->h_stage + (size_t)chunk * st->table_elems + lo;
     std::memcpy(stage, &st->cur_ptrs[lo], n * sizeof(void*));
-    KV_HIP(st, hipMemcpyAsync(st->d_slot[slot] + lo, stage, n * sizeof(void*), hipMemcpyHostToDevice, st->stream));
-    KV_HIP(st, hipEventRecord(st->stage_ev[chunk], st->stream));
+    KV_HIP(st, hipMemcpyAsync(st->d_slot[slot] + lo, stage, n * sizeof(void*), hipMemcpyHostToDevice, stream));
+    KV_HIP(st, hipEventRecord(st->stage_ev[chunk], stream));
     st->stage_busy[chunk] = true;
     std::memcpy(&st->mirror[slot][lo], &st->cur_ptrs[lo], n * sizeof(void*));
     for (int sgm = s0; sgm < s1; ++sgm) st->row_valid[slot][sgm] = 1;
@@ -167,12 +180,57 @@ int table_for(kv_store* st, int s0, int s1, const void* const** table_out) {
     return KV_OK;
 }
 
-int issue_copy_out(kv_store* st, int key, void* dst, int what) {
+int issue_copy_out(kv_store* st, int key, void* dst, int what, hipStream_t stream) {
     const float* base = what == 0 ? st->w : what == 1 ? st->m : st->s;
     const int64_t n = st->plan.numel[key];
     if (n == 0) return KV_OK;
     KV_HIP(st, hipMemcpyAsync(dst, base + st->plan.key_arena_off[key], (size_t)n * sizeof(float), hipMemcpyDefault,
-                              st->stream));
+                              stream));
+    return KV_OK;
+}
+
+// One fused kernel launch over tiles [tile_lo, tile_hi), which belong to segments [s0, s1).
+int launch_tiles(kv_store* st, int s0, int s1, int64_t tile_lo, int64_t tile_hi, hipStream_t stream, int log_a,
+                 int log_b) {
+    if (tile_hi <= tile_lo) return KV_OK;
+    const void* const* table = nullptr;
+    int rc = table_for(st, s0, s1, stream, &table);
+    if (rc != KV_OK) return rc;
+    KvLaunchArgs a{};
+    a.tiles = st->d_tiles;
+    a.gptrs = table;
+    a.w = st->w;
+    a.m = st->m;
+    a.s = st->s;
+    a.tile_lo = tile_lo;
+    a.tile_hi = tile_hi;
+    a.W = st->W;
+    a.xcd_remap = st->xcd_remap;
+    a.lr = st->p.lr;
+    a.momentum = st->p.momentum;
+    a.wd = st->p.wd;
+    a.rescale = st->rescale;
+    KvKernelSel sel{};
+    sel.grad_f16 = st->plan.grad_dtype == KV_F16;
+    sel.W = st->W;
+    sel.pairwise = st->p.reduce_order == KV_REDUCE_PAIRWISE;
+    sel.keep_sum = (st->flags & KV_FLAG_KEEP_SUM) != 0;
+    sel.unroll = st->unroll;
+    sel.nontemporal = st->nontemporal;
+    const int64_t ntiles = tile_hi - tile_lo;
+    int64_t span = ntiles;
+    if (st->xcd_remap) span = ((ntiles + 7) / 8) * 8;
+    int64_t grid = span;
+    if (st->wg_per_cu > 0) {
+        int64_t cap = (int64_t)st->num_cus * st->wg_per_cu;
+        if (st->xcd_remap) cap = (cap + 7) / 8 * 8;
+        if (grid > cap) grid = cap;
+    }
+    if (grid > 0x7FFFFFF0LL) grid = 0x7FFFFFF0LL;       // multiple of 8; the tile loop strides
+    KV_HIP(st, kv_launch_fused(sel, a, (unsigned)grid, stream));
+    if ((int)st->log.size() < LOG_CAP) st->log.emplace_back(log_a, log_b);
+    else st->log[(size_t)(st->launches_total % LOG_CAP)] = std::make_pair(log_a, log_b);
+    ++st->launches_total;
     return KV_OK;
 }
 
@@ -180,54 +238,72 @@ int issue_copy_out(kv_store* st, int key, void* dst, int what) {
 int launch_run(kv_store* st, int first, int n) {
     const int s0 = st->plan.units[first].seg_begin;
     const int s1 = st->plan.units[first + n - 1].seg_end;
-    const int64_t tile_lo = st->unit_tile_begin[first];
-    const int64_t tile_hi = st->unit_tile_begin[first + n];
-    if (tile_hi > tile_lo) {
-        const void* const* table = nullptr;
-        int rc = table_for(st, s0, s1, &table);
-        if (rc != KV_OK) return rc;
-        KvLaunchArgs a{};
-        a.tiles = st->d_tiles;
-        a.gptrs = table;
-        a.w = st->w;
-        a.m = st->m;
-        a.s = st->s;
-        a.tile_lo = tile_lo;
-        a.tile_hi = tile_hi;
-        a.W = st->W;
-        a.xcd_remap = st->xcd_remap;
-        a.lr = st->p.lr;
-        a.momentum = st->p.momentum;
-        a.wd = st->p.wd;
-        a.rescale = st->rescale;
-        KvKernelSel sel{};
-        sel.grad_f16 = st->plan.grad_dtype == KV_F16;
-        sel.W = st->W;
-        sel.pairwise = st->p.reduce_order == KV_REDUCE_PAIRWISE;
-        sel.keep_sum = (st->flags & KV_FLAG_KEEP_SUM) != 0;
-        sel.unroll = st->unroll;
-        sel.nontemporal = st->nontemporal;
-        const int64_t ntiles = tile_hi - tile_lo;
-        int64_t span = ntiles;
-        if (st->xcd_remap) span = ((ntiles + 7) / 8) * 8;
-        int64_t grid = span;
-        if (st->wg_per_cu > 0) {
-            int64_t cap = (int64_t)st->num_cus * st->wg_per_cu;
-            if (st->xcd_remap) cap = (cap + 7) / 8 * 8;
-            if (grid > cap) grid = cap;
-        }
-        if (grid > 0x7FFFFFF0LL) grid = 0x7FFFFFF0LL;       // multiple of 8; the tile loop strides
-        KV_HIP(st, kv_launch_fused(sel, a, (unsigned)grid, st->stream));
-        if ((int)st->log.size() < LOG_CAP) st->log.emplace_back(first, n);
-        else st->log[(size_t)(st->launches_total % LOG_CAP)] = std::make_pair(first, n);
-        ++st->launches_total;
-    }
+    int rc = launch_tiles(st, s0, s1, st->unit_tile_begin[first], st->unit_tile_begin[first + n], st->stream, first, n);
+    if (rc != KV_OK) return rc;
     for (int u = first; u < first + n; ++u) {
         for (const Deferred& d : st->deferred[u]) {
-            int rc = issue_copy_out(st, d.key, d.dst, d.what);
+            rc = issue_copy_out(st, d.key, d.dst, d.what, st->stream);
             if (rc != KV_OK) return rc;
         }
         st->deferred[u].clear();
+    }
+    return KV_OK;
+}
+
+// Stream on which a key's work runs: the store's stream, or in the concurrent schedule the
+// lane the key hashes to (key mod number of lanes).
+hipStream_t key_stream(const kv_store* st, int key) {
+    if (st->schedule == KV_SCHED_CONCURRENT && !st->lanes.empty()) return st->lanes[(size_t)key % st->lanes.size()];
+    return st->stream;
+}
+
+// Makes a lane wait for everything already issued on the store's stream (the producer of the
+// gradients, earlier sets and pulls).  Inside a list push the event is recorded once and every
+// lane waits for it once: nothing new can have been issued on the store's stream meanwhile.
+int fork_to(kv_store* st, hipStream_t lane, int lane_index) {
+    if (lane == st->stream) return KV_OK;
+    if (st->in_list) {
+        if (!st->list_forked) {
+            KV_HIP(st, hipEventRecord(st->fork_ev, st->stream));
+            st->list_forked = true;
+            st->lane_waited.assign(st->lanes.size(), 0);
+        }
+        if (lane_index >= 0 && st->lane_waited[(size_t)lane_index]) return KV_OK;
+        KV_HIP(st, hipStreamWaitEvent(lane, st->fork_ev, 0));
+        if (lane_index >= 0) st->lane_waited[(size_t)lane_index] = 1;
+        return KV_OK;
+    }
+    KV_HIP(st, hipEventRecord(st->fork_ev, st->stream));
+    KV_HIP(st, hipStreamWaitEvent(lane, st->fork_ev, 0));
+    return KV_OK;
+}
+
+int lane_of(const kv_store* st, int key) {
+    if (st->schedule == KV_SCHED_CONCURRENT && !st->lanes.empty()) return (int)((size_t)key % st->lanes.size());
+    return -1;
+}
+
+int barrier_all(kv_store* st) {
+    for (hipStream_t l : st->lanes) KV_HIP(st, hipStreamSynchronize(l));
+    KV_HIP(st, hipStreamSynchronize(st->stream));
+    for (int i = 0; i < NSTAGE; ++i) st->stage_busy[i] = false;
+    st->since_barrier = 0;
+    return KV_OK;
+}
+
+// Funneled and concurrent schedules: the key is launched by its own push.
+int launch_key(kv_store* st, int key) {
+    const int sgm = st->plan.key_seg[key];
+    hipStream_t stream = key_stream(st, key);
+    int rc = fork_to(st, stream, lane_of(st, key));
+    if (rc != KV_OK) return rc;
+    rc = launch_tiles(st, sgm, sgm + 1, st->seg_tile_begin[sgm], st->seg_tile_begin[sgm + 1], stream, key, 0);
+    if (rc != KV_OK) return rc;
+    if (st->schedule == KV_SCHED_FUNNEL) {
+        // the issuing thread does the aggregation itself: nothing else is started before it is done
+        KV_HIP(st, hipStreamSynchronize(stream));
+    } else if (st->outstanding > 0 && ++st->since_barrier >= st->outstanding) {
+        return barrier_all(st);
     }
     return KV_OK;
 }
@@ -282,7 +358,10 @@ int pull_common(kv_store* st, int key, void* dst, int what) {
         st->deferred[st->plan.key_unit[key]].push_back(Deferred{key, dst, what});
         return KV_OK;
     }
-    return issue_copy_out(st, key, dst, what);
+    hipStream_t stream = key_stream(st, key);
+    rc = fork_to(st, stream, lane_of(st, key));
+    if (rc != KV_OK) return rc;
+    return issue_copy_out(st, key, dst, what, stream);
 }
 
 int set_common(kv_store* st, int key, const void* src, float* arena) {
@@ -295,8 +374,11 @@ int set_common(kv_store* st, int key, const void* src, float* arena) {
         set_err(st->err, "set of key %d: null source", key);
         return KV_ERR_ARG;
     }
+    hipStream_t stream = key_stream(st, key);
+    rc = fork_to(st, stream, lane_of(st, key));
+    if (rc != KV_OK) return rc;
     KV_HIP(st, hipMemcpyAsync(arena + st->plan.key_arena_off[key], src, (size_t)n * sizeof(float), hipMemcpyDefault,
-                              st->stream));
+                              stream));
     return KV_OK;
 }
 
@@ -449,7 +531,7 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
 
     std::vector<KvTile> tiles;
     try {
-        kv_plan_tiles(st->plan, st->tile_elems, tiles, st->unit_tile_begin);
+        kv_plan_tiles(st->plan, st->tile_elems, tiles, st->unit_tile_begin, st->seg_tile_begin);
         st->table_elems = st->plan.seg_key.size() * (size_t)W;
         st->cur_ptrs.assign(st->table_elems, nullptr);
         for (int i = 0; i < NSLOT; ++i) {
@@ -480,6 +562,7 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     for (int i = 0; i < NSLOT; ++i) KV_INIT_HIP(hipMalloc((void**)&st->d_slot[i], st->table_elems * sizeof(void*)));
     KV_INIT_HIP(hipHostMalloc((void**)&st->h_stage, (size_t)NSTAGE * st->table_elems * sizeof(void*), hipHostMallocDefault));
     for (int i = 0; i < NSTAGE; ++i) KV_INIT_HIP(hipEventCreateWithFlags(&st->stage_ev[i], hipEventDisableTiming));
+    KV_INIT_HIP(hipEventCreateWithFlags(&st->fork_ev, hipEventDisableTiming));
     KV_INIT_HIP(hipEventCreate(&st->t0));
     KV_INIT_HIP(hipEventCreate(&st->t1));
     // the host vector `tiles` dies at return: wait for its upload
@@ -491,6 +574,7 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
 
 void kv_destroy(kv_store* store) {
     if (!store) return;
+    for (hipStream_t l : store->lanes) (void)hipStreamSynchronize(l);
     (void)hipStreamSynchronize(store->stream);
     free_store(store);
 }
@@ -515,6 +599,10 @@ int kv_push(kv_store* store, int key, const void* const* dev_grads) {
     if (rc != KV_OK) return rc;
     rc = check_grads(store, key, dev_grads);
     if (rc != KV_OK) return rc;
+    if (store->schedule != KV_SCHED_CHAINED) {
+        record_grads(store, key, dev_grads);
+        return launch_key(store, key);
+    }
     rc = store->chain.mark(key);
     if (rc != KV_OK) {
         set_err(store->err, "key %d pushed twice before its unit ran", key);
@@ -529,6 +617,15 @@ int kv_push_list(kv_store* store, int nkeys, const int* keys, const void* const*
     if (nkeys < 0 || (nkeys > 0 && (!keys || !dev_grads))) {
         set_err(store->err, "kv_push_list: bad arguments");
         return KV_ERR_ARG;
+    }
+    if (store->schedule != KV_SCHED_CHAINED) {
+        // keys go out one by one, in list order
+        store->in_list = true;
+        store->list_forked = false;
+        int rc = KV_OK;
+        for (int i = 0; i < nkeys && rc == KV_OK; ++i) rc = kv_push(store, keys[i], dev_grads + (size_t)i * store->W);
+        store->in_list = false;
+        return rc;
     }
     // validate everything before marking anything
     for (int i = 0; i < nkeys; ++i) {
@@ -577,20 +674,63 @@ int kv_wait(kv_store* store, int key) {
             set_err(store->err, "kv_wait: key %d is pushed but its unit waits for other keys or lower units", key);
             return KV_ERR_INCOMPLETE;
         }
-        KV_HIP(store, hipStreamSynchronize(store->stream));
+        KV_HIP(store, hipStreamSynchronize(key_stream(store, key)));
         return KV_OK;
     }
     if (key != -1) {
         set_err(store->err, "kv_wait: key %d", key);
         return KV_ERR_KEY;
     }
-    KV_HIP(store, hipStreamSynchronize(store->stream));
-    for (int i = 0; i < NSTAGE; ++i) store->stage_busy[i] = false;
+    {
+        int rc = barrier_all(store);
+        if (rc != KV_OK) return rc;
+    }
     if (store->chain.pending_keys > 0 || store->chain.next_unit != 0) {
         set_err(store->err, "kv_wait: iteration incomplete (%d keys pushed but not launched, next unit %d)",
                 store->chain.pending_keys, store->chain.next_unit);
         return KV_ERR_INCOMPLETE;
     }
+    return KV_OK;
+}
+
+int kv_barrier(kv_store* store) { return store ? barrier_all(store) : KV_ERR_ARG; }
+
+int kv_set_schedule(kv_store* store, int schedule, int n_streams, int outstanding) {
+    if (!store) return KV_ERR_ARG;
+    if (schedule != KV_SCHED_CHAINED && schedule != KV_SCHED_FUNNEL && schedule != KV_SCHED_CONCURRENT) {
+        set_err(store->err, "kv_set_schedule: unknown schedule %d", schedule);
+        return KV_ERR_ARG;
+    }
+    if (schedule == KV_SCHED_CONCURRENT && (n_streams < 1 || n_streams > KV_MAX_STREAMS || outstanding < 0)) {
+        set_err(store->err, "kv_set_schedule: n_streams must be 1..%d and outstanding >= 0", KV_MAX_STREAMS);
+        return KV_ERR_ARG;
+    }
+    if (store->chain.pending_keys > 0 || store->chain.next_unit != 0) {
+        set_err(store->err, "kv_set_schedule: an iteration is in progress");
+        return KV_ERR_STATE;
+    }
+    int rc = barrier_all(store);
+    if (rc != KV_OK) return rc;
+    if (schedule == KV_SCHED_CONCURRENT) {
+        try {
+            while ((int)store->lanes.size() < n_streams) {
+                hipStream_t l = nullptr;
+                KV_HIP(store, hipStreamCreateWithFlags(&l, hipStreamNonBlocking));     // default priority
+                store->lanes.push_back(l);
+            }
+        } catch (const std::bad_alloc&) {
+            return KV_ERR_NOMEM;
+        }
+        while ((int)store->lanes.size() > n_streams) {
+            (void)hipStreamDestroy(store->lanes.back());
+            store->lanes.pop_back();
+        }
+        store->outstanding = outstanding;
+    } else {
+        store->outstanding = 0;
+    }
+    store->since_barrier = 0;
+    store->schedule = schedule;
     return KV_OK;
 }
 

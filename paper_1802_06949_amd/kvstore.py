@@ -13,6 +13,7 @@ from typing import List, Optional, Sequence, Tuple
 KV_F32, KV_F16 = 0, 1
 KV_REDUCE_SEQUENTIAL, KV_REDUCE_PAIRWISE = 0, 1
 KV_FLAG_KEEP_SUM = 1
+KV_SCHED_CHAINED, KV_SCHED_FUNNEL, KV_SCHED_CONCURRENT = 0, 1, 2
 STATUS = {0: "KV_OK", -1: "KV_ERR_ARG", -2: "KV_ERR_KEY", -3: "KV_ERR_STATE", -4: "KV_ERR_ALIGN",
           -5: "KV_ERR_INCOMPLETE", -6: "KV_ERR_HIP", -7: "KV_ERR_NOMEM"}
 
@@ -82,6 +83,8 @@ def load_library() -> ctypes.CDLL:
     sig("kv_pull_momentum", c_int, c_vp, c_int, c_vp)
     sig("kv_weights_ptr", c_int, c_vp, c_int, P(c_vp))
     sig("kv_wait", c_int, c_vp, c_int)
+    sig("kv_set_schedule", c_int, c_vp, c_int, c_int, c_int)
+    sig("kv_barrier", c_int, c_vp)
     sig("kv_store_plan", c_vp, c_vp)
     sig("kv_launch_log", c_int, c_vp, P(c_i64), P(c_int), P(c_int), c_int)
     sig("kv_timing_begin", c_int, c_vp)
@@ -307,6 +310,12 @@ class KVStore:
 
     def wait_status(self, key: int = -1) -> int:
         return self._L.kv_wait(self._h, key)
+
+    def set_schedule(self, schedule: int, n_streams: int = 1, outstanding: int = 0) -> None:
+        self._check(self._L.kv_set_schedule(self._h, schedule, n_streams, outstanding))
+
+    def barrier(self) -> None:
+        self._check(self._L.kv_barrier(self._h))
 
     # --- introspection
     def launch_log(self, cap: int = 4096) -> Tuple[int, List[Tuple[int, int]]]:

@@ -49,7 +49,7 @@ class Pair:
     """A GPU store and an oracle store with the same keys and parameters."""
 
     def __init__(self, numel: Sequence[int], W: int, grad_dtype: str, bucket_bytes: int, *, lr: float, momentum: float,
-                 wd: float, rescale: float = 0.0, order: int = 0, keep_sum: bool = True, **tuning):
+                 wd: float, rescale: float = 0.0, order: int = 0, keep_sum: bool = True, schedule=None, **tuning):
         import paper_1802_06949_amd as kv
         self.kv = kv
         self.numel = [int(n) for n in numel]
@@ -60,6 +60,8 @@ class Pair:
         self.cpu = orc.OracleStore(self.numel, W, lr=lr, momentum=momentum, wd=wd, rescale=rescale, order=order,
                                    keep_sum=keep_sum)
         self.keep_sum = keep_sum
+        if schedule is not None:
+            self.gpu.set_schedule(*schedule)
 
     def set_weights(self, weights: Sequence[np.ndarray]) -> None:
         for k, w in enumerate(weights):
@@ -117,10 +119,10 @@ class Pair:
 
 def run_config(cfg: wl.Config, steps: int, *, order: int = 0, mode: str = "list", keep_sum: bool = True,
                gen_threads: int = 8, oracle_threads: int = 1, rotate_after_first: bool = False, label: str = "",
-               **tuning) -> None:
+               schedule=None, **tuning) -> None:
     """Steps a benchmark configuration on both sides and compares after every step."""
     pair = Pair(cfg.numel, cfg.W, cfg.grad_dtype, cfg.bucket_bytes, lr=cfg.lr, momentum=cfg.momentum, wd=cfg.wd,
-                order=order, keep_sum=keep_sum, **tuning)
+                order=order, keep_sum=keep_sum, schedule=schedule, **tuning)
     try:
         pair.set_weights(wl.make_weights(cfg, gen_threads))
         grads = dev = None

@@ -1,0 +1,115 @@
+"""GPU parity of the funneled and concurrent schedules (the paper's "MPI Funneled"
+and "MPI Concurrent Communications" designs) against the same oracle: the three
+schedules differ in when and where a key's aggregation runs, never in its value."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import kv_oracle as orc
+from tests.gpu_harness import Pair, run_config
+
+pytestmark = pytest.mark.gpu
+F = np.float32
+CHAINED, FUNNEL, CONCURRENT = 0, 1, 2
+
+
+def _rng(*seed):
+    return np.random.Generator(np.random.SFC64(list(seed)))
+
+
+def _grads(numel, W, dtype, seed):
+    out = []
+    for k, n in enumerate(numel):
+        gk = [(_rng(seed, k, r).standard_normal(n, dtype=F) * F(0.01)).astype(F) for r in range(W)]
+        out.append([g.astype(np.float16) for g in gk] if dtype == "f16" else gk)
+    return out
+
+
+SCHEDULES = [(FUNNEL, 1, 0), (CONCURRENT, 1, 0), (CONCURRENT, 3, 0), (CONCURRENT, 8, 2), (CONCURRENT, 4, 5)]
+
+
+@pytest.mark.parametrize("schedule", SCHEDULES, ids=lambda s: f"sched{s[0]}-n{s[1]}-o{s[2]}")
+@pytest.mark.parametrize("mode", ["list", "each"])
+def test_resnet20_under_every_schedule(schedule, mode):
+    run_config(wl.get_config(2), 3, mode=mode, schedule=schedule, label=f"schedule {schedule}")
+
+
+@pytest.mark.parametrize("schedule", SCHEDULES, ids=lambda s: f"sched{s[0]}-n{s[1]}-o{s[2]}")
+@pytest.mark.parametrize("dtype,order", [("f32", orc.PAIRWISE), ("f16", orc.SEQUENTIAL)])
+def test_ragged_keys_under_every_schedule(schedule, dtype, order):
+    numel = [0, 1, 5, 64, 1023, 1025, 4096, 4099, 0, 20000, 7]
+    pair = Pair(numel, 5, dtype, 8192, lr=0.1, momentum=0.9, wd=1e-4, order=order, schedule=schedule)
+    try:
+        pair.set_weights([_rng(1, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        for t in range(3):
+            pair.step(_grads(numel, 5, dtype, 10 + t), mode="each", order=[int(x) for x in _rng(2, t).permutation(len(numel))])
+            pair.compare(f"{schedule} step {t}")
+    finally:
+        pair.close()
+
+
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("schedule", [(FUNNEL, 1, 0), (CONCURRENT, 4, 8)], ids=["funnel", "concurrent"])
+def test_resnet50_full_size_per_key_schedules(schedule):
+    run_config(wl.get_config(3), 2, keep_sum=False, gen_threads=16, oracle_threads=8, schedule=schedule)
+
+
+def test_per_key_launches_follow_the_push_order():
+    numel = [100, 0, 5000, 64, 3000]
+    pair = Pair(numel, 2, "f32", 1 << 20, lr=0.1, momentum=0.0, wd=0.0, schedule=(FUNNEL, 1, 0))
+    try:
+        g = _grads(numel, 2, "f32", 20)
+        order = [4, 1, 0, 3, 2]
+        pair.step(g, mode="each", order=order)
+        total, log = pair.gpu.launch_log()
+        assert log == [(k, 0) for k in order if numel[k] > 0] and total == 4    # the empty key launches nothing
+        pair.compare("funnel order")
+    finally:
+        pair.close()
+
+
+def test_switching_schedules_between_iterations():
+    numel = [100, 5000, 64, 3000, 9]
+    W = 4
+    pair = Pair(numel, W, "f32", 4096, lr=0.1, momentum=0.9, wd=1e-4)
+    try:
+        pair.set_weights([_rng(3, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        seq = [(CHAINED, 1, 0), (FUNNEL, 1, 0), (CONCURRENT, 3, 2), (CHAINED, 1, 0), (CONCURRENT, 2, 0), (FUNNEL, 1, 0)]
+        for t, sched in enumerate(seq):
+            pair.gpu.set_schedule(*sched)
+            pair.step(_grads(numel, W, "f32", 30 + t), mode="each" if t % 2 else "list")
+            pair.compare(f"after switching to {sched}")
+        # a switch in the middle of a chained iteration is refused
+        pair.gpu.set_schedule(CHAINED)
+        dev = pair.upload(_grads(numel, W, "f32", 40))
+        pair.gpu.push(0, dev[0])
+        with pytest.raises(pair.kv.KVError) as e:
+            pair.gpu.set_schedule(FUNNEL)
+        assert e.value.status == -3
+        with pytest.raises(pair.kv.KVError):
+            pair.gpu.set_schedule(CONCURRENT, 0, 0)
+        with pytest.raises(pair.kv.KVError):
+            pair.gpu.set_schedule(7)
+    finally:
+        pair.close()
+
+
+def test_concurrent_pull_then_barrier_sees_the_update():
+    import torch
+    numel = [4096, 4096, 4096]
+    pair = Pair(numel, 2, "f32", 1 << 20, lr=0.5, momentum=0.0, wd=0.0, schedule=(CONCURRENT, 3, 0))
+    try:
+        g = _grads(numel, 2, "f32", 50)
+        dev = pair.upload(g)
+        outs = [torch.zeros(n, device="cuda") for n in numel]
+        for k in range(3):
+            pair.gpu.push(k, dev[k])
+            pair.gpu.pull(k, outs[k])               # on the key's stream, after its update
+        pair.gpu.barrier()
+        pair.cpu.step(g)
+        for k in range(3):
+            assert np.array_equal(outs[k].cpu().numpy(), pair.cpu.w[k])
+    finally:
+        pair.close()
