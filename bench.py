@@ -46,6 +46,9 @@ def parse_args():
                     help="chained = one merged launch per step (headline); funnel / concurrent = one launch per key")
     ap.add_argument("--streams", type=int, default=4, help="concurrent schedule: number of streams")
     ap.add_argument("--outstanding", type=int, default=0, help="concurrent schedule: barrier after this many keys")
+    ap.add_argument("--broadcast", choices=["none", "f32", "f16"], default="none",
+                    help="also write the new weights to --replicas replica buffers per key in the same kernel")
+    ap.add_argument("--replicas", type=int, default=0, help="replica buffers per key (default: W)")
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--workgroups-per-cu", type=int, default=-1)
     ap.add_argument("--nontemporal", type=int, default=-1)
@@ -138,6 +141,14 @@ def main() -> int:
         if w.size:
             store.set_weights(k, torch.from_numpy(w).cuda())
     store.wait()
+    bcast_bytes = 0
+    if args.broadcast != "none":
+        R = args.replicas or cfg.W
+        rdt = torch.float32 if args.broadcast == "f32" else torch.float16
+        reps = [[torch.empty(n, dtype=rdt, device="cuda") for _ in range(R)] for n in cfg.numel]
+        for k in range(K):
+            store.set_broadcast(k, reps[k], args.broadcast)
+        bcast_bytes = N * R * (4 if args.broadcast == "f32" else 2)
     sched = {"chained": kv.KV_SCHED_CHAINED, "funnel": kv.KV_SCHED_FUNNEL, "concurrent": kv.KV_SCHED_CONCURRENT}[args.schedule]
     store.set_schedule(sched, args.streams, args.outstanding)
     keys = list(range(K))
@@ -159,7 +170,7 @@ def main() -> int:
 
     t_step = wall / args.steps
     agg_gbps = N * cfg.W * itemsize / t_step / 1e9
-    alg_bytes_step = cfg.algorithmic_bytes_per_step
+    alg_bytes_step = cfg.algorithmic_bytes_per_step + bcast_bytes
     launches_per_step = launches / args.steps
     alg_bytes_launch = alg_bytes_step / max(launches_per_step, 1e-9)
     launch_s = ev_ms * 1e-3 / max(launches, 1)
@@ -205,7 +216,8 @@ def main() -> int:
             "launches_per_step": launches_per_step,
             "schedule": args.schedule + (f" ({args.streams} streams, barrier every {args.outstanding} keys)"
                                          if args.schedule == "concurrent" else ""),
-            "pull": "zero-copy (weights read in place in the arena)",
+            "pull": "zero-copy (weights read in place in the arena)" if args.broadcast == "none" else
+                    f"fused broadcast to {args.replicas or cfg.W} {args.broadcast} replicas per key (+{bcast_bytes} B per step)",
         },
         "params_per_s": round(N / t_step, 1),
         "algorithmic_hbm_GBps": round(alg_bytes_step / t_step / 1e9, 2),

@@ -205,6 +205,19 @@ int kv_pull_momentum(kv_store* store, int key, void* dev_out_f32);
 int kv_weights_ptr(kv_store* store, int key, void** dev_ptr_out);
 
 /*
+ * kv_set_broadcast: the third phase of the paper's collective ("broadcast of the final result
+ * across all the GPUs", which its pull performs by copying the aggregate back into every worker's
+ * tensor), fused into the update: from the next launch on, the kernel that computes the key's new
+ * weights also writes them to n_replicas caller-owned device buffers of numel elements each, as
+ * fp32 (dtype KV_F32) or rounded to nearest-even fp16 (KV_F16).  dev_dst: host array of n_replicas
+ * device pointers, aligned to the element (16-byte alignment of all of them keeps the 128-bit path).
+ * Every key of a store must use the same n_replicas and dtype (KV_ERR_STATE otherwise); n_replicas = 0
+ * removes the key's replicas.  Blocks until the store's streams are idle.  The replicas must stay
+ * valid while pushes of the key can still launch.
+ */
+int kv_set_broadcast(kv_store* store, int key, int n_replicas, void* const* dev_dst /* host [n_replicas] */, int dtype);
+
+/*
  * kv_wait(key >= 0): blocks the host until the key's last launched update (and all
  * earlier work on the stream) is complete; KV_ERR_INCOMPLETE, without blocking, if
  * the key is pushed but its unit cannot be launched yet.

@@ -73,6 +73,49 @@ float kvo_half_to_float(uint16_t h)
     return out;
 }
 
+/*
+ * binary32 value -> IEEE binary16 bit pattern, round to nearest, ties to even; overflow goes to
+ * infinity, results below the smallest normal half are subnormal halves.  Used for the fp16
+ * replicas of the updated weights (the broadcast phase of the paper's collective, done in half
+ * precision as an extension).
+ */
+uint16_t kvo_float_to_half(float x)
+{
+    uint32_t bits;
+    memcpy(&bits, &x, sizeof bits);
+    uint16_t sign = (uint16_t)((bits >> 16) & 0x8000u);
+    uint32_t a = bits & 0x7FFFFFFFu;
+    if (a > 0x7F800000u) {                         /* nan: keep it a nan */
+        uint16_t m = (uint16_t)((a >> 13) & 0x3FFu);
+        return (uint16_t)(sign | 0x7C00u | (m ? m : 0x200u));
+    }
+    if (a >= 0x477FF000u) return (uint16_t)(sign | 0x7C00u);   /* 65520 = max half + half an ulp: rounds up to infinity; so does infinity itself */
+    if (a >= 0x38800000u) {                        /* result is a normal half (>= 2^-14) */
+        uint32_t e = (a >> 23) - 112u;             /* rebias 127 -> 15 */
+        uint32_t q = (e << 10) | ((a >> 13) & 0x3FFu);
+        uint32_t rem = a & 0x1FFFu;
+        if (rem > 0x1000u || (rem == 0x1000u && (q & 1u))) ++q;   /* a carry runs into the exponent */
+        return (uint16_t)(sign | q);
+    }
+    if (a < 0x33000000u) return sign;              /* below 2^-25: rounds to zero */
+    {                                              /* subnormal half: multiples of 2^-24 */
+        uint32_t e = a >> 23;                      /* 102 .. 112 */
+        uint32_t mant = (a & 0x7FFFFFu) | 0x800000u;
+        uint32_t shift = 126u - e;                 /* 24 .. 14 */
+        uint32_t q = mant >> shift;
+        uint32_t rem = mant & ((1u << shift) - 1u);
+        uint32_t half = 1u << (shift - 1u);
+        if (rem > half || (rem == half && (q & 1u))) ++q;
+        return (uint16_t)(sign | q);
+    }
+}
+
+/* out[i] = kvo_float_to_half(in[i]) for i in [0, n). */
+void kvo_round_to_half(const float* in, int64_t n, uint16_t* out)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = kvo_float_to_half(in[i]);
+}
+
 static float fold_sequential(const float* v, int W)
 {
     float s = v[0];

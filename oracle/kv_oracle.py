@@ -41,6 +41,8 @@ def lib() -> ctypes.CDLL:
         fp = ctypes.POINTER(ctypes.c_float)
         L.kvo_half_to_float.restype = ctypes.c_float
         L.kvo_half_to_float.argtypes = [ctypes.c_uint16]
+        L.kvo_round_to_half.restype = None
+        L.kvo_round_to_half.argtypes = [fp, ctypes.c_int64, ctypes.POINTER(ctypes.c_uint16)]
         L.kvo_reduce_key.restype = ctypes.c_int
         L.kvo_reduce_key.argtypes = [vpp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                      ctypes.c_int64, ctypes.c_int64, fp]
@@ -79,6 +81,14 @@ def _check_grads(grads: Sequence[np.ndarray]):
 
 def half_to_float(bits: int) -> float:
     return float(lib().kvo_half_to_float(bits & 0xFFFF))
+
+
+def round_to_half(x: np.ndarray) -> np.ndarray:
+    """binary32 -> binary16, round to nearest even (the value the fp16 replicas of the weights receive)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.size, dtype=np.uint16)
+    lib().kvo_round_to_half(_fptr(x), x.size, out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)))
+    return out.view(np.float16).reshape(x.shape)
 
 
 def reduce_key(grads: Sequence[np.ndarray], order: int = SEQUENTIAL) -> np.ndarray:

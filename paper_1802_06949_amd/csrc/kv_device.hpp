@@ -20,7 +20,10 @@ struct KvLaunchArgs {
     const void* const* gptrs;     // device, [num_segs * W] gradient pointers, segment-major
     float* w;                     // weight arena
     float* m;                     // momentum arena
-    float* s;                     // raw-sum arena (only read by kernels built with KEEP)
+    float* s;                     // raw-sum arena (only written by kernels built with KEEP)
+    const void* const* bcast;     // device, [num_segs * bcast_n] replica weight pointers, or null
+    int32_t bcast_n;              // replicas per key (0 = no broadcast)
+    int32_t bcast_f16;            // replicas are fp16 (rounded to nearest even) instead of fp32
     int64_t tile_lo;              // first tile of this launch
     int64_t tile_hi;              // one past the last tile
     int32_t W;

@@ -236,23 +236,57 @@ __device__ __forceinline__ void sgd_update(float s, float w, float m, float resc
     w_new = w + dw;
 }
 
+// Third phase of the paper's collective ("broadcast of the final result across all the GPUs"):
+// the updated weights also go to `n` replica buffers of the key, as fp32 or rounded to nearest-even
+// fp16, in the same pass.  row == nullptr or a null first pointer: the key has no replicas.
+struct Bcast {
+    const uint64_t KV_CONST* row;
+    int n;
+    int f16;
+};
+
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void bcast4(const Bcast& b, int64_t e, const f32x4& wn) {
+    if (b.n == 0) return;
+    if (b.f16) {
+        f16x4 h;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) h[c] = (_Float16)wn[c];
+        for (int r = 0; r < b.n; ++r) *(f16x4 KV_GLOBAL*)(b.row[r] + (uint64_t)e * 2u) = h;
+    } else {
+        for (int r = 0; r < b.n; ++r) *(f32x4 KV_GLOBAL*)(b.row[r] + (uint64_t)e * 4u) = wn;
+    }
+}
+
+__device__ __forceinline__ void bcast1(const Bcast& b, int64_t e, float wn) {
+    if (b.n == 0) return;
+    if (b.f16) {
+        for (int r = 0; r < b.n; ++r) ((_Float16 KV_GLOBAL*)b.row[r])[e] = (_Float16)wn;
+    } else {
+        for (int r = 0; r < b.n; ++r) ((float KV_GLOBAL*)b.row[r])[e] = wn;
+    }
+}
+
 // Element `k` of the tile: e = element index inside the key, wp/mp/sp point at the tile start.
 template <bool F16, int WT, bool PAIRWISE, bool KEEP>
 __device__ __forceinline__ void scalar_element(const uint64_t KV_CONST* gp, int W, int64_t e, int k,
                                                float* __restrict__ wp, float* __restrict__ mp, float* __restrict__ sp,
-                                               const KvLaunchArgs& a) {
+                                               const Bcast& bc, const KvLaunchArgs& a) {
     const float s = reduce_one<F16, WT, PAIRWISE>(gp, W, e);
     float wn, mn;
     sgd_update(s, wp[k], mp[k], a.rescale, a.lr, a.momentum, a.wd, wn, mn);
     if constexpr (KEEP) sp[k] = s;
     mp[k] = mn;
     wp[k] = wn;
+    bcast1(bc, e, wn);
 }
 
 // Updates the four elements k..k+3 of the tile whose arenas start at wp / mp / sp.
 template <bool KEEP, int NTS>
 __device__ __forceinline__ void update_store4(const float* s4, const f32x4& wv, const f32x4& mv, float* wp, float* mp,
-                                              float* sp, int k, unsigned span_bytes, const KvLaunchArgs& a) {
+                                              float* sp, int k, unsigned span_bytes, const Bcast& bc, int64_t e,
+                                              const KvLaunchArgs& a) {
     f32x4 wn, mn, sv;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -263,6 +297,7 @@ __device__ __forceinline__ void update_store4(const float* s4, const f32x4& wv, 
     if constexpr (KEEP) store_state<NTS>(sp, k, span_bytes, sv);
     store_state<NTS>(mp, k, span_bytes, mn);
     store_state<NTS>(wp, k, span_bytes, wn);
+    bcast4(bc, e, wn);
 }
 
 template <bool F16, int WT, bool PAIRWISE, bool KEEP, int U, int NTM>
@@ -329,7 +364,17 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
 
         uint64_t bits = 0;
         for (int r = 0; r < W; ++r) bits |= gp[r];
-        const bool vec_ok = (bits & 15u) == 0;
+
+        Bcast bc{nullptr, 0, a.bcast_f16};
+        if (a.bcast_n > 0) {
+            const uint64_t KV_CONST* row = (const uint64_t KV_CONST*)a.bcast + (int64_t)td.seg * a.bcast_n;
+            if (row[0] != 0) {
+                bc.row = row;
+                bc.n = a.bcast_n;
+                for (int r = 0; r < a.bcast_n; ++r) bits |= row[r];
+            }
+        }
+        const bool vec_ok = (bits & 15u) == 0;      // every gradient and replica buffer 16-byte aligned
 
         if (vec_ok && full) {
             // every gradient load of every unrolled vector is issued before the first store
@@ -344,7 +389,8 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
                 const int k = (tid + u * KV_THREADS) * NV;
 #pragma unroll
                 for (int q = 0; q < Q; ++q)
-                    update_store4<KEEP, NTS>(&s[u][4 * q], w4[u][q], m4[u][q], wp, mp, sp, k + 4 * q, span_bytes, a);
+                    update_store4<KEEP, NTS>(&s[u][4 * q], w4[u][q], m4[u][q], wp, mp, sp, k + 4 * q, span_bytes, bc,
+                                             td.seg_off + k + 4 * q, a);
             }
         } else if (vec_ok) {
             // ragged tile: whole vectors first, then at most NV-1 single elements
@@ -357,17 +403,18 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
                 for (int q = 0; q < Q; ++q) {
                     const f32x4 wv = load_state<NTL>(wp + k + 4 * q);
                     const f32x4 mv = load_state<NTL>(mp + k + 4 * q);
-                    update_store4<KEEP, NTS>(&s[4 * q], wv, mv, wp, mp, sp, k + 4 * q, span_bytes, a);
+                    update_store4<KEEP, NTS>(&s[4 * q], wv, mv, wp, mp, sp, k + 4 * q, span_bytes, bc,
+                                             td.seg_off + k + 4 * q, a);
                 }
             }
             const int rem = td.count - nvec * NV;
             if (tid < rem) {
                 const int k = nvec * NV + tid;
-                scalar_element<F16, WT, PAIRWISE, KEEP>(gp, W, td.seg_off + k, k, wp, mp, sp, a);
+                scalar_element<F16, WT, PAIRWISE, KEEP>(gp, W, td.seg_off + k, k, wp, mp, sp, bc, a);
             }
         } else {
             for (int k = tid; k < td.count; k += KV_THREADS)
-                scalar_element<F16, WT, PAIRWISE, KEEP>(gp, W, td.seg_off + k, k, wp, mp, sp, a);
+                scalar_element<F16, WT, PAIRWISE, KEEP>(gp, W, td.seg_off + k, k, wp, mp, sp, bc, a);
         }
     }
 }

@@ -79,6 +79,12 @@ struct kv_store {
 
     std::vector<std::vector<Deferred>> deferred;  // per unit
 
+    // fused broadcast of the updated weights to replica buffers
+    int bcast_n = 0;
+    int bcast_f16 = 0;
+    const void** d_bcast = nullptr;               // device, [num_segs * bcast_n]
+    std::vector<const void*> h_bcast;
+
     // schedules other than the chained one launch one key at a time
     int schedule = KV_SCHED_CHAINED;
     int outstanding = 0;                          // concurrent schedule: barrier after this many pushes (0 = never)
@@ -119,6 +125,7 @@ void free_store(kv_store* st) {
     if (st->d_tiles) (void)hipFree(st->d_tiles);
     for (int i = 0; i < NSLOT; ++i)
         if (st->d_slot[i]) (void)hipFree(st->d_slot[i]);
+    if (st->d_bcast) (void)hipFree(st->d_bcast);
     if (st->h_stage) (void)hipHostFree(st->h_stage);
     for (int i = 0; i < NSTAGE; ++i)
         if (st->stage_ev[i]) (void)hipEventDestroy(st->stage_ev[i]);
@@ -202,6 +209,9 @@ int launch_tiles(kv_store* st, int s0, int s1, int64_t tile_lo, int64_t tile_hi,
     a.w = st->w;
     a.m = st->m;
     a.s = st->s;
+    a.bcast = st->d_bcast;
+    a.bcast_n = st->d_bcast ? st->bcast_n : 0;
+    a.bcast_f16 = st->bcast_f16;
     a.tile_lo = tile_lo;
     a.tile_hi = tile_hi;
     a.W = st->W;
@@ -690,6 +700,59 @@ int kv_wait(kv_store* store, int key) {
                 store->chain.pending_keys, store->chain.next_unit);
         return KV_ERR_INCOMPLETE;
     }
+    return KV_OK;
+}
+
+int kv_set_broadcast(kv_store* store, int key, int n_replicas, void* const* dev_dst, int dtype) {
+    if (!store) return KV_ERR_ARG;
+    int rc = check_key(store, key);
+    if (rc != KV_OK) return rc;
+    if (n_replicas < 0 || n_replicas > KV_MAX_W || (n_replicas > 0 && !dev_dst) || (dtype != KV_F32 && dtype != KV_F16)) {
+        set_err(store->err, "kv_set_broadcast: bad arguments (n_replicas=%d, dtype=%d)", n_replicas, dtype);
+        return KV_ERR_ARG;
+    }
+    if (store->chain.marked[key]) {
+        set_err(store->err, "kv_set_broadcast: key %d is pushed and waits for its launch", key);
+        return KV_ERR_STATE;
+    }
+    if (n_replicas == 0 && store->bcast_n == 0) return KV_OK;
+    if (store->bcast_n != 0 && n_replicas != 0 && (n_replicas != store->bcast_n || (dtype == KV_F16) != (store->bcast_f16 != 0))) {
+        set_err(store->err, "kv_set_broadcast: every key of a store uses the same replica count and dtype (%d, %s)",
+                store->bcast_n, store->bcast_f16 ? "f16" : "f32");
+        return KV_ERR_STATE;
+    }
+    const uintptr_t mask = dtype == KV_F16 ? 1u : 3u;
+    for (int r = 0; r < n_replicas; ++r) {
+        if (!dev_dst[r] && store->plan.numel[key] > 0) {
+            set_err(store->err, "kv_set_broadcast: replica pointer %d of key %d is null", r, key);
+            return KV_ERR_ARG;
+        }
+        if ((uintptr_t)dev_dst[r] & mask) {
+            set_err(store->err, "kv_set_broadcast: replica pointer %d of key %d is not aligned to its element", r, key);
+            return KV_ERR_ALIGN;
+        }
+    }
+    // launches in flight may be reading the table
+    rc = barrier_all(store);
+    if (rc != KV_OK) return rc;
+    const size_t nseg = store->plan.seg_key.size();
+    if (store->bcast_n == 0) {
+        try {
+            store->h_bcast.assign(nseg * (size_t)n_replicas, nullptr);
+        } catch (const std::bad_alloc&) {
+            return KV_ERR_NOMEM;
+        }
+        KV_HIP(store, hipMalloc((void**)&store->d_bcast, store->h_bcast.size() * sizeof(void*)));
+        KV_HIP(store, hipMemset(store->d_bcast, 0, store->h_bcast.size() * sizeof(void*)));
+        store->bcast_n = n_replicas;
+        store->bcast_f16 = dtype == KV_F16;
+    }
+    const size_t row = (size_t)store->plan.key_seg[key] * (size_t)store->bcast_n;
+    // a key with no elements keeps a null row: it has no tiles, the kernel never looks at it
+    for (int r = 0; r < store->bcast_n; ++r)
+        store->h_bcast[row + r] = (n_replicas > 0 && store->plan.numel[key] > 0) ? dev_dst[r] : nullptr;
+    KV_HIP(store, hipMemcpy(store->d_bcast + row, &store->h_bcast[row], (size_t)store->bcast_n * sizeof(void*),
+                            hipMemcpyHostToDevice));
     return KV_OK;
 }
 

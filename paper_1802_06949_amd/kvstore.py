@@ -83,6 +83,7 @@ def load_library() -> ctypes.CDLL:
     sig("kv_pull_momentum", c_int, c_vp, c_int, c_vp)
     sig("kv_weights_ptr", c_int, c_vp, c_int, P(c_vp))
     sig("kv_wait", c_int, c_vp, c_int)
+    sig("kv_set_broadcast", c_int, c_vp, c_int, c_int, P(c_vp), c_int)
     sig("kv_set_schedule", c_int, c_vp, c_int, c_int, c_int)
     sig("kv_barrier", c_int, c_vp)
     sig("kv_store_plan", c_vp, c_vp)
@@ -310,6 +311,14 @@ class KVStore:
 
     def wait_status(self, key: int = -1) -> int:
         return self._L.kv_wait(self._h, key)
+
+    def set_broadcast(self, key: int, replicas: Sequence, dtype="f32") -> None:
+        """kv_set_broadcast: replicas is a list of tensors (or raw addresses) that receive the key's new weights."""
+        ptrs = [int(r) if isinstance(r, int) else int(r.data_ptr()) for r in replicas]
+        arr = (ctypes.c_void_p * max(len(ptrs), 1))(*ptrs)
+        self._check(self._L.kv_set_broadcast(self._h, key, len(ptrs), arr, _dtype_code(dtype)))
+        self._bcast_keep = getattr(self, "_bcast_keep", {})
+        self._bcast_keep[key] = replicas
 
     def set_schedule(self, schedule: int, n_streams: int = 1, outstanding: int = 0) -> None:
         self._check(self._L.kv_set_schedule(self._h, schedule, n_streams, outstanding))

@@ -63,6 +63,29 @@ def test_half_widening_matches_numpy_on_all_bit_patterns():
     assert np.array_equal(s.view(np.uint32), ref.view(np.uint32))
 
 
+def test_rounding_to_half_matches_numpy():
+    """The fp16 replicas of the weights are binary32 values rounded to nearest-even binary16.
+    numpy's float32 -> float16 cast is the library routine: every half round-trips, and every
+    midpoint between neighbouring halves (the ties), its two binary32 neighbours, the overflow
+    threshold, the subnormal range and three million random values agree bit for bit."""
+    h = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    f = h.view(np.float16).astype(np.float32)
+    ok = ~np.isnan(f)
+    assert np.array_equal(orc.round_to_half(f).view(np.uint16)[ok], h[ok])
+    assert np.all(np.isnan(orc.round_to_half(f[~ok])))
+    fin = np.unique(f[np.isfinite(f)])
+    mid = ((fin[:-1].astype(np.float64) + fin[1:].astype(np.float64)) / 2).astype(F)      # exact in binary32
+    special = np.array([65519.996, 65520, 65504, 65535, 1e9, -1e9, 2.0 ** -25, np.nextafter(F(2.0 ** -25), F(1)),
+                        1.5 * 2.0 ** -24, 2.0 ** -14, np.nextafter(F(2.0 ** -14), F(0)), 0.0, -0.0, np.inf, -np.inf], dtype=F)
+    cands = np.concatenate([mid, np.nextafter(mid, F(np.inf)), np.nextafter(mid, F(-np.inf)), special, -mid])
+    with np.errstate(over="ignore"):
+        assert np.array_equal(orc.round_to_half(cands).view(np.uint16), cands.astype(np.float16).view(np.uint16))
+    r = _rng(99)
+    x = r.standard_normal(3_000_000, dtype=F) * (F(10.0) ** r.integers(-9, 6, 3_000_000).astype(F))
+    with np.errstate(over="ignore"):
+        assert np.array_equal(orc.round_to_half(x).view(np.uint16), x.astype(np.float16).view(np.uint16))
+
+
 # ---------------------------------------------------------------- identical copies
 @pytest.mark.parametrize("W", [2, 4, 8, 16, 32])
 def test_identical_copies_pairwise_power_of_two_exact(W):
