@@ -74,6 +74,49 @@ def test_config5_vgg16_full_size():
     run_config(wl.get_config(5), 2, keep_sum=False, gen_threads=16, oracle_threads=8, rotate_after_first=True)
 
 
+@pytest.mark.timeout(300)
+def test_config6_inception_bn_with_the_papers_learning_rate_scaling():
+    """The paper's other ImageNet model; the learning rate is changed between steps with
+    kv_set_lr along the linear scaling the paper describes (0.1 by default, 1.0 at 256 GPUs)."""
+    cfg = wl.get_config(6)
+    pair = Pair(cfg.numel, cfg.W, cfg.grad_dtype, cfg.bucket_bytes, lr=wl.scaled_lr(8), momentum=cfg.momentum, wd=cfg.wd)
+    try:
+        pair.set_weights(wl.make_weights(cfg, 16))
+        for t, gpus in enumerate((8, 64, 256)):
+            lr = wl.scaled_lr(gpus)
+            pair.gpu.set_lr(lr)
+            pair.cpu.lr = lr
+            pair.step(wl.make_step_gradients(cfg, t, 16), oracle_threads=8)
+            pair.compare(f"inception-bn step {t} lr {lr}")
+    finally:
+        pair.close()
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("dtype,numel,W", [("f32", (1 << 30) + 517, 1), ("f16", (1 << 31) + 1029, 2)])
+def test_one_key_beyond_four_gigabytes(dtype, numel, W):
+    """Maximum sizes: element and byte offsets of a single key pass 2^31 and 2^32.
+    Values repeat a 16M-element seeded block (cheap to generate, same on both sides)."""
+    block = 1 << 24
+    reps = numel // block + 1
+
+    def tiled(seed, scale, dt):
+        b = (_rng(seed).standard_normal(block, dtype=F) * F(scale)).astype(dt)
+        return np.tile(b, reps)[:numel]
+
+    pair = Pair([64, numel, 5], W, dtype, 1 << 20, lr=0.1, momentum=0.9, wd=1e-4, keep_sum=False)
+    try:
+        gdt = np.float32 if dtype == "f32" else np.float16
+        small = lambda n, seed: [(_rng(seed, r).standard_normal(n, dtype=F) * F(0.01)).astype(gdt) for r in range(W)]
+        grads = [small(64, 71), [tiled(72 + r, 0.01, gdt) for r in range(W)], small(5, 73)]
+        pair.set_weights([_rng(74).standard_normal(64, dtype=F), tiled(75, 1.0, F), _rng(76).standard_normal(5, dtype=F)])
+        dev = pair.step(grads, oracle_threads=16)
+        pair.step(grads, dev=dev, oracle_threads=16)                   # second step: m != 0
+        pair.compare(f"{numel} elements of {dtype}")
+    finally:
+        pair.close()
+
+
 # ------------------------------------------------------------------ ragged sizes, every W path
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
 @pytest.mark.parametrize("W", [1, 2, 3, 4, 5, 7, 8, 9, 13, 16, 32, 33])

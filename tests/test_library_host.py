@@ -44,7 +44,7 @@ def _lib_plan(numel, dtype, bucket):
     return p, p.units()
 
 
-@pytest.mark.parametrize("cfg_id", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("cfg_id", [1, 2, 3, 4, 5, 6])
 def test_plan_matches_oracle_scan_on_benchmark_configs(cfg_id):
     cfg = wl.get_config(cfg_id)
     p, units = _lib_plan(cfg.numel, cfg.grad_dtype, cfg.bucket_bytes)
@@ -84,7 +84,7 @@ def test_chain_runs_ascend_whatever_the_push_order(seed):
     """The paper's ordering requirement: the order in which units run is the same
     whatever order the gradients become ready in."""
     r = _rng(78, seed)
-    cfg = wl.get_config(int(r.integers(1, 6)))
+    cfg = wl.get_config(int(r.integers(1, 7)))
     p = kv.Plan(cfg.numel, cfg.grad_dtype, cfg.bucket_bytes)
     c = kv.Chain(p)
     K, U = p.num_keys, p.num_units

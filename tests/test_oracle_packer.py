@@ -51,6 +51,7 @@ def test_itemsize_counts_one_gradient_copy():
     (3, 161, 25_557_032, 12, 10),
     (4, 161, 25_557_032, 8, 0),
     (5, 32, 138_357_544, 7, 2),
+    (6, 209, 11_194_984, 12, 0),          # Inception-BN-shaped; count follows from the layer table, not pinned
 ])
 def test_benchmark_key_sets(cfg_id, keys, params, small, large):
     cfg = wl.get_config(cfg_id)
@@ -86,3 +87,9 @@ def test_generators_are_seeded_and_independent_per_rank():
     s = wl.key_sigma(cfg3)
     assert s.min() >= 1e-4 * 0.999 and s.max() <= 1e-2 * 1.001
     assert wl.make_gradient(wl.get_config(4), 0, 0, 0).dtype == np.float16
+
+
+def test_learning_rate_scaling_goes_through_the_papers_two_points():
+    # Evaluation section: 0.1 by default, 1.0 at 256 GPUs, grown linearly with the mini-batch
+    assert wl.scaled_lr(1) == 0.1 and wl.scaled_lr(8) == 0.1
+    assert wl.scaled_lr(256) == 1.0 and wl.scaled_lr(128) == 0.5

@@ -12,7 +12,7 @@ from __future__ import annotations
 from dataclasses import dataclass, field
 from typing import Callable, Dict, List, Sequence
 
-from .keysets import KeySpec, mlp_keys, resnet20_keys, resnet50_keys, vgg16_keys
+from .keysets import KeySpec, inception_bn_keys, mlp_keys, resnet20_keys, resnet50_keys, vgg16_keys
 
 KIB = 1 << 10
 MIB = 1 << 20
@@ -77,7 +77,19 @@ def _cfg5() -> Config:
                   sigma_mode="const", sigma_lo=1e-3, sigma_hi=1e-3)
 
 
-CONFIGS: Dict[int, Callable[[], Config]] = {1: _cfg1, 2: _cfg2, 3: _cfg3, 4: _cfg4, 5: _cfg5}
+def _cfg6() -> Config:
+    """The paper's other ImageNet model, with the learning rate it uses at 256 GPUs."""
+    return Config(6, "inception_bn_w8", inception_bn_keys(), 8, "f32", 4 * MIB, lr=1.0,
+                  sigma_mode="loguniform", sigma_lo=1e-4, sigma_hi=1e-2)
+
+
+CONFIGS: Dict[int, Callable[[], Config]] = {1: _cfg1, 2: _cfg2, 3: _cfg3, 4: _cfg4, 5: _cfg5, 6: _cfg6}
+
+
+def scaled_lr(n_gpus: int, base_lr: float = 0.1, lr_at_256: float = 1.0) -> float:
+    """Learning rate grown linearly with the number of GPUs (the global mini-batch), through the two
+    points the paper states: 0.1 by default and 1.0 at 256 GPUs.  Never below the default."""
+    return max(base_lr, lr_at_256 * n_gpus / 256.0)
 
 
 def get_config(cfg_id: int) -> Config:
