@@ -49,6 +49,11 @@ def parse_args():
     ap.add_argument("--broadcast", choices=["none", "f32", "f16"], default="none",
                     help="also write the new weights to --replicas replica buffers per key in the same kernel")
     ap.add_argument("--replicas", type=int, default=0, help="replica buffers per key (default: W)")
+    ap.add_argument("--overlap", action="store_true",
+                    help="instead of the headline: engine-driven loop with synthetic backward operators on a second "
+                         "stream, reported as backward only / aggregation only / serial / overlapped")
+    ap.add_argument("--spin", type=int, default=20000, help="--overlap: multiply-adds per lane of the largest producer")
+    ap.add_argument("--engine-threads", type=int, default=2)
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--workgroups-per-cu", type=int, default=-1)
     ap.add_argument("--nontemporal", type=int, default=-1)
@@ -97,6 +102,69 @@ def cpu_baseline(cfg, weights, grads_host, seconds: float):
     return out
 
 
+def overlap_mode(args) -> int:
+    """Overlap of aggregation with (synthetic) backward compute, the paper's actual claim."""
+    import numpy as np
+    import torch
+    import workloads as wl
+    import paper_1802_06949_amd as kv
+    from paper_1802_06949_amd.engine import Engine
+    from paper_1802_06949_amd.training_loop import EngineLoop
+
+    cfg = wl.get_config(args.config)
+    K, W = len(cfg.keys), cfg.W
+    tdt = torch.float32 if cfg.grad_dtype == "f32" else torch.float16
+    store = kv.KVStore(cfg.numel, W, cfg.grad_dtype, cfg.bucket_bytes, lr=cfg.lr, momentum=cfg.momentum, wd=cfg.wd,
+                       descending=True)
+    grads = wl.make_step_gradients(cfg, 0, args.gen_threads)
+    staged = [torch.from_numpy(np.stack(g)).cuda() for g in grads]
+    live = [torch.zeros_like(s) for s in staged]
+    del grads
+    side = torch.cuda.Stream()
+    eng = Engine(args.engine_threads)
+    biggest = max(cfg.numel)
+    spin = [int(args.spin * n / biggest) for n in cfg.numel]
+    loop = EngineLoop(store, eng, staged, live, side.cuda_stream, spin)
+    lists = store.make_push_list(list(range(K - 1, -1, -1)), [[live[k][r] for r in range(W)] for k in range(K - 1, -1, -1)])
+
+    def timed(fn, reps):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps * 1e3
+
+    def serial():
+        loop.backward_only()
+        side.synchronize()
+        store.push_list(lists)
+        store.wait()
+
+    def overlapped():
+        loop.step()
+        store.wait()
+
+    reps = args.steps
+    res = {
+        "mode": "overlap",
+        "workload": cfg.name,
+        "spin": args.spin,
+        "engine_threads": args.engine_threads,
+        "backward_only_ms": round(timed(lambda: (loop.backward_only(), side.synchronize()), reps), 4),
+        "aggregation_only_ms": round(timed(lambda: (store.push_list(lists), store.wait()), reps), 4),
+        "serial_ms": round(timed(serial, reps), 4),
+        "overlapped_ms": round(timed(overlapped, reps), 4),
+    }
+    loop.close()
+    eng.close()
+    store.close()
+    print(json.dumps(res))
+    return 0
+
+
 def main() -> int:
     args = parse_args()
     if args.gpus != 1:
@@ -114,6 +182,8 @@ def main() -> int:
         return 1
     kv.load_library()                                   # fails loudly if the HIP library is not built
     torch.cuda.set_device(0)
+    if args.overlap:
+        return overlap_mode(args)
 
     cfg = wl.get_config(args.config)
     K = len(cfg.keys)

@@ -61,7 +61,11 @@ enum kv_status {
 enum kv_dtype { KV_F32 = 0, KV_F16 = 1 };                 /* gradient element type   */
 enum kv_reduce_order { KV_REDUCE_SEQUENTIAL = 0,          /* s = g_0; s += g_r, r=1.. */
                        KV_REDUCE_PAIRWISE   = 1 };        /* balanced tree, see below */
-enum kv_flags { KV_FLAG_KEEP_SUM = 1u };                  /* also store s (kv_pull_grad) */
+enum kv_flags { KV_FLAG_KEEP_SUM   = 1u,                  /* also store s (kv_pull_grad) */
+                KV_FLAG_DESCENDING = 2u };                /* units run from the last one down to unit 0: the
+                                                             order in which a backward pass produces gradients
+                                                             (last layer first).  Still a function of the key
+                                                             set alone, so the same on every worker. */
 
 /*
  * The paper's three ways of embedding the aggregation into the worker's task flow
@@ -146,9 +150,13 @@ int64_t kv_plan_arena_numel(const kv_plan* plan);              /* fp32 elements 
  * iteration; it returns 1 while it yields a run and 0 when nothing is ready.
  * A unit is ready when all its keys are marked; a ready unit still waits for every
  * lower unit of the same iteration (the paper's chain of write dependencies).
+ * kv_chain_set_descending(1) reverses the order (last unit first, every unit waits for the
+ * higher ones); a run is still reported by its lowest unit and its length.  Allowed only
+ * between iterations (KV_ERR_STATE otherwise).
  */
 int     kv_chain_create(kv_chain** out, const kv_plan* plan /* must outlive the chain */);
 void    kv_chain_destroy(kv_chain* chain);
+int     kv_chain_set_descending(kv_chain* chain, int descending);
 int     kv_chain_mark(kv_chain* chain, int key);
 int     kv_chain_next_run(kv_chain* chain, int* first_unit_out, int* n_units_out);
 int     kv_chain_pending_keys(const kv_chain* chain);          /* marked, unit not yet run */
@@ -217,6 +225,10 @@ int kv_weights_ptr(kv_store* store, int key, void** dev_ptr_out);
  */
 int kv_set_broadcast(kv_store* store, int key, int n_replicas, void* const* dev_dst /* host [n_replicas] */, int dtype);
 
+/* Makes the store's stream wait (on the GPU, not the host) for hip_event (a hipEvent_t recorded on
+ * another stream): the read dependency of later pushes on gradients that the other stream produces. */
+int kv_wait_event(kv_store* store, void* hip_event);
+
 /*
  * kv_wait(key >= 0): blocks the host until the key's last launched update (and all
  * earlier work on the stream) is complete; KV_ERR_INCOMPLETE, without blocking, if
@@ -244,7 +256,7 @@ int kv_barrier(kv_store* store);
  * The plan in use (owned by the store). */
 const kv_plan* kv_store_plan(const kv_store* store);
 /* Launch log: total number of kernel launches so far in *total_out; the most
- * recent min(total, cap) launches, oldest first, as (first_unit, n_units) pairs. */
+ * recent min(total, cap) launches, oldest first, as (lowest unit, n_units) pairs. */
 int kv_launch_log(const kv_store* store, int64_t* total_out, int* first_unit_out, int* n_units_out, int cap);
 /* GPU time between two points of the store's stream, measured with HIP events:
  * begin records an event; end records another, waits for it and returns the

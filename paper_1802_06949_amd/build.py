@@ -42,11 +42,13 @@ def _jobs():
     jobs.append((os.path.join(CSRC, "kv_dispatch.hip"), os.path.join(OBJ, "kv_dispatch.o"), DEVICE))
     jobs.append((os.path.join(CSRC, "kv_plan.cpp"), os.path.join(OBJ, "kv_plan.o"), []))
     jobs.append((os.path.join(CSRC, "kv_store.cpp"), os.path.join(OBJ, "kv_store.o"), []))
+    jobs.append((os.path.join(CSRC, "kv_engine.cpp"), os.path.join(OBJ, "kv_engine.o"), []))
     return jobs
 
 
 def _deps():
-    return [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(HERE, "..", "include", "kv.h")]
+    inc = os.path.join(HERE, "..", "include")
+    return [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(inc, f) for f in os.listdir(inc)]
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
@@ -72,7 +74,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
     objs = [obj for _, obj, _ in _jobs()]
     if todo or not os.path.exists(LIB):
         tmp = LIB + f".tmp{os.getpid()}"
-        run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
+        run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread", "-o", tmp, *objs])
         os.replace(tmp, LIB)
     return LIB
 

@@ -23,7 +23,31 @@ __global__ void __launch_bounds__(KV_THREADS) kv_copy_kernel(f32x4* __restrict__
     const size_t stride = (size_t)gridDim.x * KV_THREADS;
     for (size_t i = (size_t)blockIdx.x * KV_THREADS + threadIdx.x; i < nvec; i += stride) dst[i] = src[i];
 }
+// Stand-in for a compute-bound backward operator: every lane first runs `spin` dependent
+// multiply-adds (no memory traffic), then copies its share.  The spun value can never equal
+// the sentinel, but the compiler cannot know that, so the loop stays.
+__global__ void __launch_bounds__(KV_THREADS) kv_busy_copy_kernel(f32x4* __restrict__ dst, const f32x4* __restrict__ src,
+                                                                  size_t nvec, int spin) {
+    float x = 1.0f + 1e-7f * (float)threadIdx.x;
+    for (int i = 0; i < spin; ++i) x = x * 0.9999999f + 1e-9f;
+    const size_t stride = (size_t)gridDim.x * KV_THREADS;
+    for (size_t i = (size_t)blockIdx.x * KV_THREADS + threadIdx.x; i < nvec; i += stride) {
+        f32x4 v = src[i];
+        if (x == -12345.0f) v.x = x;
+        dst[i] = v;
+    }
+}
 }  // namespace
+
+hipError_t kv_launch_busy_copy(void* dst, const void* src, size_t bytes, int spin, hipStream_t stream) {
+    const size_t nvec = bytes / 16;
+    if (nvec == 0) return hipSuccess;
+    size_t blocks = (nvec + KV_THREADS - 1) / KV_THREADS;
+    if (blocks > 256u * 8u) blocks = 256u * 8u;
+    hipLaunchKernelGGL(kv_busy_copy_kernel, dim3((unsigned)blocks), dim3(KV_THREADS), 0, stream,
+                       static_cast<f32x4*>(dst), static_cast<const f32x4*>(src), nvec, spin);
+    return hipGetLastError();
+}
 
 hipError_t kv_launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream) {
     const size_t nvec = bytes / 16;

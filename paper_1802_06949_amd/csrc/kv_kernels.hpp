@@ -18,3 +18,7 @@ hipError_t kv_launch_fused(const KvKernelSel& sel, const KvLaunchArgs& args, uns
 
 // Plain float4 grid-stride copy of `bytes` bytes (multiple of 16).
 hipError_t kv_launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
+
+// Copy preceded by `spin` dependent multiply-adds per lane (a compute-bound stand-in for a
+// backward operator).
+hipError_t kv_launch_busy_copy(void* dst, const void* src, size_t bytes, int spin, hipStream_t stream);

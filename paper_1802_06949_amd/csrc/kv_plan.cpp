@@ -113,16 +113,19 @@ int kv_chain::mark(int key) {
 
 bool kv_chain::next_run(int* first, int* n) {
     const int U = (int)plan->units.size();
-    if (pending[next_unit] != 0) return false;
-    *first = next_unit;
-    while (next_unit < U && pending[next_unit] == 0) {
-        const auto& u = plan->units[next_unit];
-        pending[next_unit] = (int)u.keys.size();
+    auto unit_at = [&](int pos) { return descending ? U - 1 - pos : pos; };
+    if (pending[unit_at(next_unit)] != 0) return false;
+    const int pos0 = next_unit;
+    while (next_unit < U && pending[unit_at(next_unit)] == 0) {
+        const int ui = unit_at(next_unit);
+        const auto& u = plan->units[ui];
+        pending[ui] = (int)u.keys.size();
         for (int k : u.keys) marked[k] = 0;
         pending_keys -= (int)u.keys.size();
         ++next_unit;
     }
-    *n = next_unit - *first;
+    *n = next_unit - pos0;
+    *first = descending ? U - next_unit : pos0;      // lowest unit of the run
     if (next_unit == U) {
         next_unit = 0;
         ++iteration;

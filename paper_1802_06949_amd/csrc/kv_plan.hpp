@@ -41,11 +41,13 @@ struct kv_chain {
     const kv_plan* plan = nullptr;
     std::vector<int> pending;        // per unit: keys still missing for its next run
     std::vector<uint8_t> marked;     // per key
-    int next_unit = 0;
+    int next_unit = 0;               // position in the launch order (0 = start of an iteration)
     int pending_keys = 0;
     int64_t iteration = 0;
+    bool descending = false;         // launch order runs from the last unit down to unit 0
 
     void reset(const kv_plan* p);
     int mark(int key);                          // kv_status
+    // Next run of ready units: *first is its LOWEST unit index, *n its length.
     bool next_run(int* first, int* n);
 };

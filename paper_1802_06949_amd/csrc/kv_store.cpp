@@ -460,6 +460,13 @@ int kv_chain_create(kv_chain** out, const kv_plan* plan) {
 }
 
 void kv_chain_destroy(kv_chain* chain) { delete chain; }
+int kv_chain_set_descending(kv_chain* chain, int descending) {
+    if (!chain) return KV_ERR_ARG;
+    if (chain->pending_keys > 0 || chain->next_unit != 0) return KV_ERR_STATE;
+    chain->descending = descending != 0;
+    return KV_OK;
+}
+
 int kv_chain_mark(kv_chain* chain, int key) { return chain ? chain->mark(key) : KV_ERR_ARG; }
 
 int kv_chain_next_run(kv_chain* chain, int* first_unit_out, int* n_units_out) {
@@ -478,7 +485,7 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
         return KV_ERR_ARG;
     }
     *out = nullptr;
-    if (!params || W < 1 || W > KV_MAX_W || (flags & ~(unsigned)KV_FLAG_KEEP_SUM)) {
+    if (!params || W < 1 || W > KV_MAX_W || (flags & ~(unsigned)(KV_FLAG_KEEP_SUM | KV_FLAG_DESCENDING))) {
         set_err(g_err, "kv_init: bad arguments (params=%p, W=%d, flags=%u)", (const void*)params, W, flags);
         return KV_ERR_ARG;
     }
@@ -496,6 +503,7 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
         return rc;
     }
     st->chain.reset(&st->plan);
+    st->chain.descending = (flags & KV_FLAG_DESCENDING) != 0;
     st->W = W;
     st->flags = flags;
     st->p = *params;
@@ -753,6 +761,12 @@ int kv_set_broadcast(kv_store* store, int key, int n_replicas, void* const* dev_
         store->h_bcast[row + r] = (n_replicas > 0 && store->plan.numel[key] > 0) ? dev_dst[r] : nullptr;
     KV_HIP(store, hipMemcpy(store->d_bcast + row, &store->h_bcast[row], (size_t)store->bcast_n * sizeof(void*),
                             hipMemcpyHostToDevice));
+    return KV_OK;
+}
+
+int kv_wait_event(kv_store* store, void* hip_event) {
+    if (!store || !hip_event) return KV_ERR_ARG;
+    KV_HIP(store, hipStreamWaitEvent(store->stream, static_cast<hipEvent_t>(hip_event), 0));
     return KV_OK;
 }
 

@@ -13,6 +13,7 @@ from typing import List, Optional, Sequence, Tuple
 KV_F32, KV_F16 = 0, 1
 KV_REDUCE_SEQUENTIAL, KV_REDUCE_PAIRWISE = 0, 1
 KV_FLAG_KEEP_SUM = 1
+KV_FLAG_DESCENDING = 2
 KV_SCHED_CHAINED, KV_SCHED_FUNNEL, KV_SCHED_CONCURRENT = 0, 1, 2
 STATUS = {0: "KV_OK", -1: "KV_ERR_ARG", -2: "KV_ERR_KEY", -3: "KV_ERR_STATE", -4: "KV_ERR_ALIGN",
           -5: "KV_ERR_INCOMPLETE", -6: "KV_ERR_HIP", -7: "KV_ERR_NOMEM"}
@@ -67,6 +68,7 @@ def load_library() -> ctypes.CDLL:
     sig("kv_plan_arena_numel", c_i64, c_vp)
     sig("kv_chain_create", c_int, P(c_vp), c_vp)
     sig("kv_chain_destroy", None, c_vp)
+    sig("kv_chain_set_descending", c_int, c_vp, c_int)
     sig("kv_chain_mark", c_int, c_vp, c_int)
     sig("kv_chain_next_run", c_int, c_vp, P(c_int), P(c_int))
     sig("kv_chain_pending_keys", c_int, c_vp)
@@ -179,6 +181,9 @@ class Chain:
             self._L.kv_chain_destroy(self._h)
             self._h = None
 
+    def set_descending(self, descending: bool) -> int:
+        return self._L.kv_chain_set_descending(self._h, 1 if descending else 0)
+
     def mark(self, key: int) -> int:
         return self._L.kv_chain_mark(self._h, key)
 
@@ -225,7 +230,8 @@ class KVStore:
 
     def __init__(self, key_numel: Sequence[int], W: int, grad_dtype="f32", bucket_bytes: int = 1 << 22, *,
                  lr: float, momentum: float = 0.0, wd: float = 0.0, rescale: float = 0.0,
-                 reduce_order: int = KV_REDUCE_SEQUENTIAL, keep_sum: bool = False, stream: Optional[int] = None,
+                 reduce_order: int = KV_REDUCE_SEQUENTIAL, keep_sum: bool = False, descending: bool = False,
+                 stream: Optional[int] = None,
                  unroll: int = 0, workgroups_per_cu: int = -1, nontemporal: int = -1, xcd_remap: int = -1):
         self._L = load_library()
         self._h = None
@@ -242,7 +248,8 @@ class KVStore:
         t = _Tuning(unroll, workgroups_per_cu, nontemporal, xcd_remap)
         h = ctypes.c_void_p()
         rc = self._L.kv_init(ctypes.byref(h), n, arr, self.grad_dtype, self.W, int(bucket_bytes), ctypes.byref(p),
-                             KV_FLAG_KEEP_SUM if keep_sum else 0, ctypes.byref(t), ctypes.c_void_p(self.stream))
+                             (KV_FLAG_KEEP_SUM if keep_sum else 0) | (KV_FLAG_DESCENDING if descending else 0),
+                             ctypes.byref(t), ctypes.c_void_p(self.stream))
         if rc != 0:
             raise KVError(rc, _global_error(self._L))
         self._h = h

@@ -20,10 +20,17 @@ def _rng(*seed):
     return np.random.Generator(np.random.SFC64(list(seed)))
 
 
+def _declared(*headers):
+    names = set()
+    for h in headers:
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(kv_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
+
+
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "kv.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    names = sorted(set(re.findall(r"\b(kv_[a-z_0-9]+)\s*\(", header)))
+    names = _declared("kv.h", "kv_engine.h")
     assert len(names) >= 30
     lib = ctypes.CDLL(kv.library_path())
     for n in names:
@@ -31,12 +38,10 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_binding_covers_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "kv.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    names = set(re.findall(r"\b(kv_[a-z_0-9]+)\s*\(", header))
     src = open(os.path.join(ROOT, "paper_1802_06949_amd", "kvstore.py")).read()
-    for n in names:
-        assert f'"{n}"' in src, f"{n} has no ctypes signature in the binding"
+    src += open(os.path.join(ROOT, "paper_1802_06949_amd", "engine.py")).read()
+    for n in _declared("kv.h", "kv_engine.h"):
+        assert f'"{n}"' in src or f"L.{n}" in src, f"{n} has no ctypes signature in the binding"
 
 
 def _lib_plan(numel, dtype, bucket):
@@ -99,6 +104,31 @@ def test_chain_runs_ascend_whatever_the_push_order(seed):
             assert covered == list(range(len(covered)))
         assert covered == list(range(U))
         assert c.pending_keys == 0 and c.next_unit == 0
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_descending_chain_runs_from_the_last_unit_down(seed):
+    r = _rng(79, seed)
+    cfg = wl.get_config(int(r.integers(1, 7)))
+    p = kv.Plan(cfg.numel, cfg.grad_dtype, cfg.bucket_bytes)
+    c = kv.Chain(p)
+    assert c.set_descending(True) == 0
+    K, U = p.num_keys, p.num_units
+    for it in range(2):
+        covered = []
+        for k in r.permutation(K):
+            assert c.mark(int(k)) == 0
+            for lowest, n in c.drain():
+                covered += list(range(lowest + n - 1, lowest - 1, -1))
+        assert covered == list(range(U - 1, -1, -1))
+    # keys pushed last layer first (the order a backward pass produces them): every unit
+    # launches as soon as its own keys are in
+    launches = []
+    for k in range(K - 1, -1, -1):
+        c.mark(k)
+        launches += c.drain()
+    assert len(launches) == U and all(n == 1 for _, n in launches)
+    assert c.mark(0) == 0 and c.set_descending(False) == -3          # not in the middle of an iteration
 
 
 def test_chain_in_order_list_is_one_run():
