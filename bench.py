@@ -54,6 +54,9 @@ def parse_args():
                          "stream, reported as backward only / aggregation only / serial / overlapped")
     ap.add_argument("--spin", type=int, default=20000, help="--overlap: multiply-adds per lane of the largest producer")
     ap.add_argument("--engine-threads", type=int, default=2)
+    ap.add_argument("--flat-grads", action="store_true",
+                    help="each rank's gradients of all keys live in ONE buffer (keys at 256-byte aligned offsets) "
+                         "instead of one allocation per key and rank")
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--workgroups-per-cu", type=int, default=-1)
     ap.add_argument("--nontemporal", type=int, default=-1)
@@ -198,7 +201,23 @@ def main() -> int:
     dev_sets = []
     for s in range(nsets):
         g = wl.make_step_gradients(cfg, s, args.gen_threads)
-        dev_sets.append([[torch.from_numpy(a).cuda() for a in gk] for gk in g])
+        if args.flat_grads:
+            offs, cur = [], 0
+            for n in cfg.numel:
+                offs.append(cur)
+                cur += (n * itemsize + 255) // 256 * 256 // itemsize
+            flats = [torch.empty(cur, dtype=tdt, device="cuda") for _ in range(cfg.W)]
+            dset = []
+            for k, gk in enumerate(g):
+                row = []
+                for r, a in enumerate(gk):
+                    v = flats[r][offs[k]:offs[k] + a.size]
+                    v.copy_(torch.from_numpy(a))
+                    row.append(v)
+                dset.append(row)
+            dev_sets.append(dset)
+        else:
+            dev_sets.append([[torch.from_numpy(a).cuda() for a in gk] for gk in g])
         if s == 0:
             host_sets.append(g)
         del g
