@@ -57,6 +57,8 @@ def parse_args():
     ap.add_argument("--flat-grads", action="store_true",
                     help="each rank's gradients of all keys live in ONE buffer (keys at 256-byte aligned offsets) "
                          "instead of one allocation per key and rank")
+    ap.add_argument("--rank-skew", type=int, default=0,
+                    help="--flat-grads: rank r's buffer starts r * this many bytes into its allocation (multiple of 16)")
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--workgroups-per-cu", type=int, default=-1)
     ap.add_argument("--nontemporal", type=int, default=-1)
@@ -206,7 +208,8 @@ def main() -> int:
             for n in cfg.numel:
                 offs.append(cur)
                 cur += (n * itemsize + 255) // 256 * 256 // itemsize
-            flats = [torch.empty(cur, dtype=tdt, device="cuda") for _ in range(cfg.W)]
+            skew = args.rank_skew // itemsize
+            flats = [torch.empty(cur + cfg.W * skew, dtype=tdt, device="cuda")[r * skew:] for r in range(cfg.W)]
             dset = []
             for k, gk in enumerate(g):
                 row = []
@@ -274,6 +277,13 @@ def main() -> int:
             store.pull(k, outs[k])
         store.wait()
         extra["pull_copy_all_keys_ms"] = (time.perf_counter() - t1) * 1e3
+        store.pull_list(keys, outs)
+        store.wait()
+        t1 = time.perf_counter()
+        for _ in range(20):
+            store.pull_list(keys, outs)
+        store.wait()
+        extra["pull_list_all_keys_ms"] = (time.perf_counter() - t1) * 1e3 / 20
 
     if args.calib_copy > 0:
         nb = 1 << 30

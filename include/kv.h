@@ -208,6 +208,11 @@ int kv_push_list(kv_store* store, int nkeys, const int* keys /* host */, const v
 int kv_pull(kv_store* store, int key, void* dev_out_f32);
 int kv_pull_grad(kv_store* store, int key, void* dev_out_f32);
 int kv_pull_momentum(kv_store* store, int key, void* dev_out_f32);
+/* List form of kv_pull (the paper's pull takes lists of keys and tensors): dev_out_f32 is a host
+ * array of nkeys device pointers, 4-byte aligned (16-byte alignment keeps the 128-bit path).  Keys
+ * that are not waiting for a launch are gathered by one kernel per run of keys that are neighbours
+ * in the arena (all keys: one launch); otherwise the list is served key by key as kv_pull would. */
+int kv_pull_list(kv_store* store, int nkeys, const int* keys /* host */, void* const* dev_out_f32 /* host */);
 /* Zero-copy pull: device address of the key's weights inside the arena (numel fp32,
  * 16-byte aligned, valid until kv_destroy; contents change with every step). */
 int kv_weights_ptr(kv_store* store, int key, void** dev_ptr_out);

@@ -37,7 +37,34 @@ __global__ void __launch_bounds__(KV_THREADS) kv_busy_copy_kernel(f32x4* __restr
         dst[i] = v;
     }
 }
+// Gather of whole keys out of an arena: tile t of the store's tile table is copied to
+// dst[segment of t] + its offset inside the key.  One workgroup per tile.
+__global__ void __launch_bounds__(KV_THREADS) kv_gather_kernel(const KvTile* __restrict__ tiles, int64_t tile_lo,
+                                                               const float* __restrict__ arena,
+                                                               float* const* __restrict__ dst) {
+    const KvTile td = tiles[tile_lo + blockIdx.x];
+    const float* __restrict__ src = arena + td.arena_off;
+    float* __restrict__ out = dst[td.seg] + td.seg_off;
+    const int tid = threadIdx.x;
+    if ((reinterpret_cast<uintptr_t>(out) & 15u) == 0) {
+        const int nvec = td.count >> 2;
+        for (int v = tid; v < nvec; v += KV_THREADS)
+            reinterpret_cast<f32x4*>(out)[v] = reinterpret_cast<const f32x4*>(src)[v];
+        const int k = (nvec << 2) + tid;
+        if (k < td.count) out[k] = src[k];
+    } else {
+        for (int k = tid; k < td.count; k += KV_THREADS) out[k] = src[k];
+    }
+}
 }  // namespace
+
+hipError_t kv_launch_gather(const KvTile* tiles, int64_t tile_lo, int64_t tile_hi, const float* arena,
+                            float* const* dst_table, hipStream_t stream) {
+    if (tile_hi <= tile_lo) return hipSuccess;
+    hipLaunchKernelGGL(kv_gather_kernel, dim3((unsigned)(tile_hi - tile_lo)), dim3(KV_THREADS), 0, stream, tiles, tile_lo,
+                       arena, dst_table);
+    return hipGetLastError();
+}
 
 hipError_t kv_launch_busy_copy(void* dst, const void* src, size_t bytes, int spin, hipStream_t stream) {
     const size_t nvec = bytes / 16;

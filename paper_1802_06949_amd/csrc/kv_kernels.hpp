@@ -22,3 +22,8 @@ hipError_t kv_launch_copy(void* dst, const void* src, size_t bytes, hipStream_t 
 // Copy preceded by `spin` dependent multiply-adds per lane (a compute-bound stand-in for a
 // backward operator).
 hipError_t kv_launch_busy_copy(void* dst, const void* src, size_t bytes, int spin, hipStream_t stream);
+
+// Copies the keys whose tiles are [tile_lo, tile_hi) from an arena to dst_table[segment] (device
+// table of one destination pointer per segment), one workgroup per tile.
+hipError_t kv_launch_gather(const KvTile* tiles, int64_t tile_lo, int64_t tile_hi, const float* arena,
+                            float* const* dst_table, hipStream_t stream);

@@ -85,6 +85,8 @@ struct kv_store {
     const void** d_bcast = nullptr;               // device, [num_segs * bcast_n]
     std::vector<const void*> h_bcast;
 
+    float** d_gather = nullptr;                   // device, [num_segs]: destinations of a list pull
+
     // schedules other than the chained one launch one key at a time
     int schedule = KV_SCHED_CHAINED;
     int outstanding = 0;                          // concurrent schedule: barrier after this many pushes (0 = never)
@@ -126,6 +128,7 @@ void free_store(kv_store* st) {
     for (int i = 0; i < NSLOT; ++i)
         if (st->d_slot[i]) (void)hipFree(st->d_slot[i]);
     if (st->d_bcast) (void)hipFree(st->d_bcast);
+    if (st->d_gather) (void)hipFree(st->d_gather);
     if (st->h_stage) (void)hipHostFree(st->h_stage);
     for (int i = 0; i < NSTAGE; ++i)
         if (st->stage_ev[i]) (void)hipEventDestroy(st->stage_ev[i]);
@@ -578,6 +581,7 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     if (!tiles.empty())
         KV_INIT_HIP(hipMemcpyAsync(st->d_tiles, tiles.data(), tiles.size() * sizeof(KvTile), hipMemcpyHostToDevice, st->stream));
     for (int i = 0; i < NSLOT; ++i) KV_INIT_HIP(hipMalloc((void**)&st->d_slot[i], st->table_elems * sizeof(void*)));
+    KV_INIT_HIP(hipMalloc((void**)&st->d_gather, st->plan.seg_key.size() * sizeof(float*)));
     KV_INIT_HIP(hipHostMalloc((void**)&st->h_stage, (size_t)NSTAGE * st->table_elems * sizeof(void*), hipHostMallocDefault));
     for (int i = 0; i < NSTAGE; ++i) KV_INIT_HIP(hipEventCreateWithFlags(&st->stage_ev[i], hipEventDisableTiming));
     KV_INIT_HIP(hipEventCreateWithFlags(&st->fork_ev, hipEventDisableTiming));
@@ -674,6 +678,67 @@ int kv_push_list(kv_store* store, int nkeys, const int* keys, const void* const*
 int kv_pull(kv_store* store, int key, void* dev_out_f32) { return pull_common(store, key, dev_out_f32, 0); }
 int kv_pull_momentum(kv_store* store, int key, void* dev_out_f32) { return pull_common(store, key, dev_out_f32, 1); }
 int kv_pull_grad(kv_store* store, int key, void* dev_out_f32) { return pull_common(store, key, dev_out_f32, 2); }
+
+int kv_pull_list(kv_store* store, int nkeys, const int* keys, void* const* dev_out_f32) {
+    if (!store) return KV_ERR_ARG;
+    if (nkeys < 0 || (nkeys > 0 && (!keys || !dev_out_f32))) {
+        set_err(store->err, "kv_pull_list: bad arguments");
+        return KV_ERR_ARG;
+    }
+    const size_t nseg = store->plan.seg_key.size();
+    bool simple = store->schedule != KV_SCHED_CONCURRENT;
+    std::vector<uint8_t> want;
+    try {
+        want.assign(nseg, 0);
+    } catch (const std::bad_alloc&) {
+        return KV_ERR_NOMEM;
+    }
+    for (int i = 0; i < nkeys; ++i) {
+        int rc = check_key(store, keys[i]);
+        if (rc != KV_OK) return rc;
+        if (!dev_out_f32[i] && store->plan.numel[keys[i]] > 0) {
+            set_err(store->err, "kv_pull_list: null destination for key %d", keys[i]);
+            return KV_ERR_ARG;
+        }
+        if ((uintptr_t)dev_out_f32[i] & 3u) {
+            set_err(store->err, "kv_pull_list: destination of key %d is not aligned to 4 bytes", keys[i]);
+            return KV_ERR_ALIGN;
+        }
+        const int sgm = store->plan.key_seg[keys[i]];
+        if (store->chain.marked[keys[i]] || want[(size_t)sgm]) simple = false;    // pending push, or listed twice
+        want[(size_t)sgm] = 1;
+    }
+    if (!simple) {                      // one by one: queued behind pending launches, or on the keys' own streams
+        for (int i = 0; i < nkeys; ++i) {
+            int rc = pull_common(store, keys[i], dev_out_f32[i], 0);
+            if (rc != KV_OK) return rc;
+        }
+        return KV_OK;
+    }
+    // destinations go to the device through a pinned staging chunk, then one gather per run of
+    // consecutive segments
+    const int chunk = store->stage_next;
+    store->stage_next = (store->stage_next + 1) % NSTAGE;
+    if (store->stage_busy[chunk]) {
+        KV_HIP(store, hipEventSynchronize(store->stage_ev[chunk]));
+        store->stage_busy[chunk] = false;
+    }
+    const void** stage = store->h_stage + (size_t)chunk * store->table_elems;     // table_elems >= nseg
+    for (size_t sgm = 0; sgm < nseg; ++sgm) stage[sgm] = nullptr;
+    for (int i = 0; i < nkeys; ++i) stage[(size_t)store->plan.key_seg[keys[i]]] = dev_out_f32[i];
+    KV_HIP(store, hipMemcpyAsync(store->d_gather, stage, nseg * sizeof(float*), hipMemcpyHostToDevice, store->stream));
+    KV_HIP(store, hipEventRecord(store->stage_ev[chunk], store->stream));
+    store->stage_busy[chunk] = true;
+    for (size_t a = 0; a < nseg;) {
+        if (!want[a]) { ++a; continue; }
+        size_t b = a;
+        while (b < nseg && want[b]) ++b;
+        KV_HIP(store, kv_launch_gather(store->d_tiles, store->seg_tile_begin[a], store->seg_tile_begin[b], store->w,
+                                       store->d_gather, store->stream));
+        a = b;
+    }
+    return KV_OK;
+}
 
 int kv_weights_ptr(kv_store* store, int key, void** dev_ptr_out) {
     if (!store || !dev_ptr_out) return KV_ERR_ARG;

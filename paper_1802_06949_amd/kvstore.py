@@ -81,6 +81,7 @@ def load_library() -> ctypes.CDLL:
     sig("kv_push", c_int, c_vp, c_int, P(c_vp))
     sig("kv_push_list", c_int, c_vp, c_int, P(c_int), P(c_vp))
     sig("kv_pull", c_int, c_vp, c_int, c_vp)
+    sig("kv_pull_list", c_int, c_vp, c_int, P(c_int), P(c_vp))
     sig("kv_pull_grad", c_int, c_vp, c_int, c_vp)
     sig("kv_pull_momentum", c_int, c_vp, c_int, c_vp)
     sig("kv_weights_ptr", c_int, c_vp, c_int, P(c_vp))
@@ -301,6 +302,12 @@ class KVStore:
     # --- pull
     def pull(self, key: int, out) -> None:
         self._check(self._L.kv_pull(self._h, key, ctypes.c_void_p(out.data_ptr())))
+
+    def pull_list(self, keys: Sequence[int], outs: Sequence) -> None:
+        n = len(keys)
+        karr = (ctypes.c_int * max(n, 1))(*[int(k) for k in keys])
+        parr = (ctypes.c_void_p * max(n, 1))(*[int(o.data_ptr()) for o in outs])
+        self._check(self._L.kv_pull_list(self._h, n, karr, parr))
 
     def pull_grad(self, key: int, out) -> None:
         self._check(self._L.kv_pull_grad(self._h, key, ctypes.c_void_p(out.data_ptr())))

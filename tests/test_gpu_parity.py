@@ -334,6 +334,42 @@ def test_pull_before_the_bucket_is_complete_is_deferred():
         pair.close()
 
 
+@pytest.mark.parametrize("schedule", [None, (1, 1, 0), (2, 3, 0)], ids=["chained", "funnel", "concurrent"])
+def test_list_pull_gathers_whole_keys(schedule):
+    import torch
+    numel = [0, 1, 5, 64, 1023, 1025, 4096, 4099, 0, 20000, 7]
+    pair = Pair(numel, 2, "f32", 8192, lr=0.1, momentum=0.9, wd=1e-4, schedule=schedule)
+    try:
+        pair.set_weights([_rng(9, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        pair.step(_grads(numel, 2, "f32", 650))
+        K = len(numel)
+        for keys, mis in ((list(range(K)), 0), ([9, 2, 3, 6], 0), ([1, 2, 4, 5, 10], 1), ([3, 3], 0)):
+            bufs = [torch.full((numel[k] + 8,), 7.0, device="cuda") for k in keys]
+            outs = [b[mis:mis + numel[k]] for b, k in zip(bufs, keys)]
+            pair.gpu.pull_list(keys, outs)
+            pair.gpu.wait()
+            for k, o, b in zip(keys, outs, bufs):
+                assert np.array_equal(o.cpu().numpy().view(np.uint32), pair.cpu.w[k].view(np.uint32)), (keys, k)
+                assert torch.all(b[mis + numel[k]:] == 7.0) and torch.all(b[:mis] == 7.0)   # nothing outside the key
+        # a listed key that still waits for its launch is served after that launch
+        if schedule is None:
+            g = _grads(numel, 2, "f32", 651)
+            dev = pair.upload(g)
+            outs = [torch.zeros(numel[k], device="cuda") for k in range(K)]
+            pair.gpu.push(3, dev[3])
+            pair.gpu.pull_list(list(range(K)), outs)
+            for k in range(K):
+                if k != 3:
+                    pair.gpu.push(k, dev[k])
+            pair.gpu.wait()
+            pair.cpu.step(g)
+            assert np.array_equal(outs[3].cpu().numpy(), pair.cpu.w[3])
+        with pytest.raises(pair.kv.KVError):
+            pair.gpu.pull_list([0, 99], [torch.zeros(1, device="cuda")] * 2)
+    finally:
+        pair.close()
+
+
 def test_large_key_waits_for_lower_units():
     """Chain order: a ready unit still waits for every lower unit."""
     numel = [16, 4096, 16]                               # bucket {0, 2} is unit 0, key 1 (large) is unit 1
