@@ -465,3 +465,68 @@ def test_zero_copy_weights_pointer_and_timing():
         assert np.array_equal(out.cpu().numpy(), pair.cpu.w[1])
     finally:
         pair.close()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_sessions_of_pushes_and_pulls(seed):
+    """Model-based: a random interleaving of single pushes (in any order, running ahead into the
+    next iteration for units that have already launched), pulls (some of them before the key's
+    unit can launch) and learning-rate changes between iterations, mirrored on the oracle."""
+    import torch
+    r = _rng(4242, seed)
+    numel = [int(x) for x in r.choice([1, 7, 64, 300, 1024, 1500, 4096, 5000, 9000], size=int(r.integers(3, 12)))]
+    K, W = len(numel), int(r.choice([1, 2, 3, 8]))
+    dtype = "f32" if seed % 2 == 0 else "f16"
+    bucket = int(r.choice([1, 4096, 16384, 1 << 30]))
+    pair = Pair(numel, W, dtype, bucket, lr=0.1, momentum=0.9, wd=1e-4, descending=bool(seed % 3 == 0))
+    try:
+        pair.set_weights([_rng(seed, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        plan = pair.gpu.plan
+        unit_of = [plan.key(k)[0] for k in range(K)]
+        pulls = []                                   # (tensor, expected values)
+        keep = []
+        iters = 4
+        pushed_in_iter = [0] * K                     # how many iterations each key has been pushed for
+        launched_iter = [0] * plan.num_units         # how many times each unit has launched (model of the chain)
+        pending = [set() for _ in range(plan.num_units)]
+        U = plan.num_units
+        order_units = list(range(U - 1, -1, -1)) if seed % 3 == 0 else list(range(U))
+        pos = 0                                      # position of the chain in order_units
+        steps = 0
+        while min(pushed_in_iter) < iters and steps < 10000:
+            steps += 1
+            k = int(r.integers(0, K))
+            u = unit_of[k]
+            can_push = pushed_in_iter[k] < iters and k not in pending[u] and pushed_in_iter[k] == launched_iter[u]
+            if can_push:
+                t = pushed_in_iter[k]
+                g = [(_rng(seed, 7, t, k, rr).standard_normal(numel[k], dtype=F) * F(0.01)) for rr in range(W)]
+                if dtype == "f16":
+                    g = [x.astype(np.float16) for x in g]
+                dev = [to_device(x) for x in g]
+                keep.append(dev)
+                pair.gpu.push(k, dev)
+                pair.cpu.step_one_key(k, g)
+                pushed_in_iter[k] += 1
+                pending[u].add(k)
+                keys_of_u = set(plan.unit(u)[0])
+                # model of the chain: launch while the unit at the chain position is complete
+                while pending[order_units[pos]] == set(plan.unit(order_units[pos])[0]):
+                    uu = order_units[pos]
+                    pending[uu] = set()
+                    launched_iter[uu] += 1
+                    pos = (pos + 1) % U
+            if r.random() < 0.3:
+                kk = int(r.integers(0, K))
+                out = torch.zeros(numel[kk], device="cuda")
+                pair.gpu.pull(kk, out)               # may be queued behind the key's launch
+                pulls.append((out, pair.cpu.w[kk].copy()))
+        assert min(pushed_in_iter) == iters, "the model got stuck"
+        pair.gpu.wait()
+        total, log = pair.gpu.launch_log()
+        assert sum(n for _, n in log) == U * iters
+        for out, ref in pulls:
+            assert np.array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+        pair.compare(f"random session {seed}")
+    finally:
+        pair.close()
