@@ -108,8 +108,8 @@ typedef struct kv_sgd_params {
  *   nontemporal       cache policy: bit 0 = gradient loads carry the non-temporal hint; plus the policy
  *                     of the stores of w', m' (and s): 0 = plain, 4 = non-temporal, 8 = write through L2;
  *                     one of 0, 1, 5, 9; -1 = default
- *   xcd_remap         1 = tiles are dealt to the 8 XCDs in contiguous ranges, 0 = round robin,
- *                     -1 = default
+ *   xcd_remap         how tiles are dealt to the 8 XCDs: 0 = one by one, round robin; 1 = eight contiguous
+ *                     ranges, one per XCD; G > 1 = blocks of G consecutive tiles per XCD; -1 = default
  */
 typedef struct kv_tuning {
     int unroll;

@@ -319,15 +319,18 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
     const uint64_t KV_CONST* table = (const uint64_t KV_CONST*)a.gptrs;
 
     const int64_t ntiles = a.tile_hi - a.tile_lo;
-    // With xcd_remap, consecutive workgroup ids (which the hardware deals round-robin
-    // to the 8 XCDs) are sent to 8 contiguous tile ranges, one per XCD.
-    const int64_t chunk = (ntiles + 7) >> 3;
-    const int64_t span = a.xcd_remap ? chunk * 8 : ntiles;
+    // The hardware deals consecutive workgroup ids round-robin to the 8 XCDs.  xcd_remap = 1 sends
+    // them to 8 contiguous tile ranges, one per XCD; xcd_remap = G > 1 gives every XCD blocks of G
+    // consecutive tiles (rows of 8 G tiles, block x of a row to XCD x); 0 leaves the tiles dealt
+    // one by one.
+    const int64_t blk = a.xcd_remap == 1 ? (ntiles + 7) >> 3 : a.xcd_remap;
+    const int64_t span = a.xcd_remap ? (ntiles + 8 * blk - 1) / (8 * blk) * (8 * blk) : ntiles;
 
     for (int64_t i = blockIdx.x; i < span; i += gridDim.x) {
         int64_t t = i;
         if (a.xcd_remap) {
-            t = (i & 7) * chunk + (i >> 3);
+            const int64_t row = i / (8 * blk), within = i - row * (8 * blk);
+            t = row * (8 * blk) + (within & 7) * blk + (within >> 3);
             if (t >= ntiles) continue;
         }
         struct { int32_t seg, count; int64_t arena_off, seg_off; } td;

@@ -232,7 +232,10 @@ int launch_tiles(kv_store* st, int s0, int s1, int64_t tile_lo, int64_t tile_hi,
     sel.nontemporal = st->nontemporal;
     const int64_t ntiles = tile_hi - tile_lo;
     int64_t span = ntiles;
-    if (st->xcd_remap) span = ((ntiles + 7) / 8) * 8;
+    if (st->xcd_remap) {
+        const int64_t G = st->xcd_remap == 1 ? (ntiles + 7) / 8 : st->xcd_remap;
+        span = (ntiles + 8 * G - 1) / (8 * G) * (8 * G);
+    }
     int64_t grid = span;
     if (st->wg_per_cu > 0) {
         int64_t cap = (int64_t)st->num_cus * st->wg_per_cu;
@@ -514,18 +517,18 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     st->stream = static_cast<hipStream_t>(hip_stream);
 
     // Defaults from sweeps on MI355X.  Non-temporal gradient loads keep the streamed gradients
-    // from evicting w and m out of the memory-side cache; contiguous tile ranges per XCD and
-    // (for fp32 gradients) write-through stores of w', m' are worth a few percent each.
+    // from evicting w and m out of the memory-side cache; giving every XCD blocks of 64 consecutive
+    // tiles and (for fp32 gradients) write-through stores of w', m' are worth a few percent each.
     const bool f16 = grad_dtype == KV_F16;
     st->unroll = 1;
     st->wg_per_cu = 0;
     st->nontemporal = f16 ? 1 : 9;
-    st->xcd_remap = 1;
+    st->xcd_remap = 64;
     if (tuning) {
         if (tuning->unroll != 0) st->unroll = tuning->unroll;
         if (tuning->workgroups_per_cu >= 0) st->wg_per_cu = tuning->workgroups_per_cu;
         if (tuning->nontemporal >= 0) st->nontemporal = tuning->nontemporal;
-        if (tuning->xcd_remap >= 0) st->xcd_remap = tuning->xcd_remap ? 1 : 0;
+        if (tuning->xcd_remap >= 0) st->xcd_remap = tuning->xcd_remap;
     }
     const int nt = st->nontemporal;
     if ((st->unroll != 1 && st->unroll != 2 && st->unroll != 4) || !(nt == 0 || nt == 1 || nt == 5 || nt == 9)) {
