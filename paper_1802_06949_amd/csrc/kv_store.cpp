@@ -233,8 +233,12 @@ int launch_tiles(kv_store* st, int s0, int s1, int64_t tile_lo, int64_t tile_hi,
     const int64_t ntiles = tile_hi - tile_lo;
     int64_t span = ntiles;
     if (st->xcd_remap) {
-        const int64_t G = st->xcd_remap == 1 ? (ntiles + 7) / 8 : st->xcd_remap;
-        span = (ntiles + 8 * G - 1) / (8 * G) * (8 * G);
+        // a block never exceeds an eighth of the launch, so a small launch (one key, a small model)
+        // does not start workgroups that find no tile
+        const int64_t eighth = (ntiles + 7) / 8;
+        const int64_t blk = st->xcd_remap == 1 || st->xcd_remap > eighth ? eighth : st->xcd_remap;
+        a.xcd_remap = (int32_t)blk;
+        span = (ntiles + 8 * blk - 1) / (8 * blk) * (8 * blk);
     }
     int64_t grid = span;
     if (st->wg_per_cu > 0) {
