@@ -260,6 +260,18 @@ def main() -> int:
     wall = time.perf_counter() - t0
     ev_ms, launches = store.timing_end()
 
+    # per-step times from a second, separate pass: an event after every step costs about 2 us per
+    # step, so it stays out of the timed region above
+    step_ms = []
+    if args.schedule == "chained":
+        store.timing_begin()
+        for i in range(min(args.steps, 500)):
+            store.push_list(lists[i % nsets])
+            store.timing_mark()
+        store.wait()
+        store.timing_end()
+        step_ms = sorted(store.timing_intervals())
+
     t_step = wall / args.steps
     agg_gbps = N * cfg.W * itemsize / t_step / 1e9
     alg_bytes_step = cfg.algorithmic_bytes_per_step + bcast_bytes
@@ -331,6 +343,8 @@ def main() -> int:
             "traffic": read_traffic(cfg.name),
             "algorithmic_bytes_per_launch": alg_bytes_launch,
             "avg_launch_us": round(launch_s * 1e6, 3),
+            "median_step_us_with_event_per_step": round(step_ms[len(step_ms) // 2] * 1e3, 3) if step_ms else None,
+            "min_step_us_with_event_per_step": round(step_ms[0] * 1e3, 3) if step_ms else None,
             "launches_timed": launches,
         },
     }

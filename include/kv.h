@@ -85,6 +85,7 @@ enum kv_schedule { KV_SCHED_CHAINED = 0, KV_SCHED_FUNNEL = 1, KV_SCHED_CONCURREN
 
 #define KV_MAX_W 256
 #define KV_MAX_STREAMS 64
+#define KV_MAX_TIMING_MARKS 8192
 
 /*
  * Optimizer parameters.  rescale <= 0 selects 1.0f / (float)W, computed once in
@@ -268,6 +269,12 @@ int kv_launch_log(const kv_store* store, int64_t* total_out, int* first_unit_out
  * elapsed milliseconds and the number of kernel launches issued in between. */
 int kv_timing_begin(kv_store* store);
 int kv_timing_end(kv_store* store, float* ms_out, int64_t* launches_out);
+/* Between begin and end, kv_timing_mark records one more event on the store's stream (at most
+ * KV_MAX_TIMING_MARKS of them; it does not wait).  After kv_timing_end, kv_timing_intervals writes
+ * the milliseconds from begin to the first mark and between consecutive marks into ms_out (host,
+ * at most cap values) and returns how many it wrote: per-step times without a host wait per step. */
+int kv_timing_mark(kv_store* store);
+int kv_timing_intervals(kv_store* store, float* ms_out, int cap);
 /* Plain streaming copy kernel (float4 grid-stride) of `bytes` bytes (multiple of 16,
  * both pointers 16-byte aligned) on hip_stream: the known-size kernel against which
  * hardware byte counters are calibrated. */

@@ -104,6 +104,8 @@ struct kv_store {
     hipEvent_t t0 = nullptr, t1 = nullptr;
     int64_t launches_at_begin = 0;
     bool timing_active = false;
+    std::vector<hipEvent_t> marks;               // kv_timing_mark: events between begin and end
+    size_t marks_used = 0;
 
     std::string err;
 };
@@ -134,6 +136,7 @@ void free_store(kv_store* st) {
         if (st->stage_ev[i]) (void)hipEventDestroy(st->stage_ev[i]);
     for (hipStream_t l : st->lanes) (void)hipStreamDestroy(l);
     if (st->fork_ev) (void)hipEventDestroy(st->fork_ev);
+    for (hipEvent_t e : st->marks) (void)hipEventDestroy(e);
     if (st->t0) (void)hipEventDestroy(st->t0);
     if (st->t1) (void)hipEventDestroy(st->t1);
     delete st;
@@ -905,7 +908,48 @@ int kv_timing_begin(kv_store* store) {
     KV_HIP(store, hipEventRecord(store->t0, store->stream));
     store->launches_at_begin = store->launches_total;
     store->timing_active = true;
+    store->marks_used = 0;
     return KV_OK;
+}
+
+int kv_timing_mark(kv_store* store) {
+    if (!store) return KV_ERR_ARG;
+    if (!store->timing_active) {
+        set_err(store->err, "kv_timing_mark without kv_timing_begin");
+        return KV_ERR_STATE;
+    }
+    if (store->marks_used == store->marks.size()) {
+        if (store->marks.size() >= (size_t)KV_MAX_TIMING_MARKS) {
+            set_err(store->err, "kv_timing_mark: more than %d marks", KV_MAX_TIMING_MARKS);
+            return KV_ERR_STATE;
+        }
+        hipEvent_t e = nullptr;
+        KV_HIP(store, hipEventCreate(&e));
+        try {
+            store->marks.push_back(e);
+        } catch (const std::bad_alloc&) {
+            (void)hipEventDestroy(e);
+            return KV_ERR_NOMEM;
+        }
+    }
+    KV_HIP(store, hipEventRecord(store->marks[store->marks_used], store->stream));
+    ++store->marks_used;
+    return KV_OK;
+}
+
+int kv_timing_intervals(kv_store* store, float* ms_out, int cap) {
+    if (!store || (cap > 0 && !ms_out)) return KV_ERR_ARG;
+    if (store->timing_active) {
+        set_err(store->err, "kv_timing_intervals before kv_timing_end");
+        return KV_ERR_STATE;
+    }
+    int n = 0;
+    hipEvent_t prev = store->t0;
+    for (size_t i = 0; i < store->marks_used && n < cap; ++i, ++n) {
+        KV_HIP(store, hipEventElapsedTime(&ms_out[n], prev, store->marks[i]));
+        prev = store->marks[i];
+    }
+    return n;
 }
 
 int kv_timing_end(kv_store* store, float* ms_out, int64_t* launches_out) {

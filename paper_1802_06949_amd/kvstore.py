@@ -93,6 +93,8 @@ def load_library() -> ctypes.CDLL:
     sig("kv_launch_log", c_int, c_vp, P(c_i64), P(c_int), P(c_int), c_int)
     sig("kv_timing_begin", c_int, c_vp)
     sig("kv_timing_end", c_int, c_vp, P(ctypes.c_float), P(c_i64))
+    sig("kv_timing_mark", c_int, c_vp)
+    sig("kv_timing_intervals", c_int, c_vp, P(ctypes.c_float), c_int)
     sig("kv_copy_bytes", c_int, c_vp, c_vp, c_sz, c_vp)
     sig("kv_last_error", ctypes.c_char_p, c_vp)
     _lib = L
@@ -357,6 +359,16 @@ class KVStore:
         ms, n = ctypes.c_float(), ctypes.c_int64()
         self._check(self._L.kv_timing_end(self._h, ctypes.byref(ms), ctypes.byref(n)))
         return ms.value, n.value
+
+    def timing_mark(self) -> None:
+        self._check(self._L.kv_timing_mark(self._h))
+
+    def timing_intervals(self, cap: int = 8192) -> List[float]:
+        buf = (ctypes.c_float * cap)()
+        n = self._L.kv_timing_intervals(self._h, buf, cap)
+        if n < 0:
+            raise KVError(n, self.last_error())
+        return [buf[i] for i in range(n)]
 
     def last_error(self) -> str:
         return self._L.kv_last_error(self._h).decode()

@@ -456,8 +456,13 @@ def test_zero_copy_weights_pointer_and_timing():
         g = _grads(numel, 2, "f32", 1000)
         pair.gpu.timing_begin()
         pair.step(g)
+        pair.gpu.timing_mark()
+        dev = pair.step(g)
+        pair.step(g, dev=dev)
+        pair.gpu.timing_mark()
         ms, launches = pair.gpu.timing_end()
-        assert launches == 1 and ms > 0
+        iv = pair.gpu.timing_intervals()
+        assert launches == 3 and ms > 0 and len(iv) == 2 and all(x > 0 for x in iv) and sum(iv) <= ms * 1.001
         ptr = pair.gpu.weights_ptr(1)
         assert ptr % 16 == 0
         out = torch.empty(5000, device="cuda")
