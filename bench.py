@@ -44,6 +44,8 @@ def parse_args():
     ap.add_argument("--pull-copy", action="store_true", help="also time a copying pull of every key (reported apart)")
     ap.add_argument("--schedule", choices=["chained", "funnel", "concurrent"], default="chained",
                     help="chained = one merged launch per step (headline); funnel / concurrent = one launch per key")
+    ap.add_argument("--push-mode", choices=["list", "each"], default="list",
+                    help="list = one kv_push_list per step (headline); each = one kv_push per key, in key order")
     ap.add_argument("--streams", type=int, default=4, help="concurrent schedule: number of streams")
     ap.add_argument("--outstanding", type=int, default=0, help="concurrent schedule: barrier after this many keys")
     ap.add_argument("--broadcast", choices=["none", "f32", "f16"], default="none",
@@ -245,6 +247,24 @@ def main() -> int:
     store.set_schedule(sched, args.streams, args.outstanding)
     keys = list(range(K))
     lists = [store.make_push_list(keys, d) for d in dev_sets]
+    if args.push_mode == "each":
+        import ctypes
+        W = cfg.W
+        rows = [[(ctypes.c_void_p * W)(*[int(t.data_ptr()) for t in d[k]]) for k in keys] for d in dev_sets]
+        push, h = store._L.kv_push, store._h
+
+        class _Each:                                    # same call shape as push_list below
+            def __init__(self, r):
+                self.r = r
+
+        def push_each(pl):
+            for k, row in enumerate(pl.r):
+                rc = push(h, k, row)
+                if rc != 0:
+                    raise kv.KVError(rc, store.last_error())
+
+        lists = [_Each(r) for r in rows]
+        store.push_list = push_each
 
     for i in range(args.warmup):
         store.push_list(lists[i % nsets])
@@ -325,6 +345,7 @@ def main() -> int:
             "gradient_sets_cycled": nsets,
             "units": store.plan.num_units,
             "launches_per_step": launches_per_step,
+            "push_mode": args.push_mode,
             "schedule": args.schedule + (f" ({args.streams} streams, barrier every {args.outstanding} keys)"
                                          if args.schedule == "concurrent" else ""),
             "pull": "zero-copy (weights read in place in the arena)" if args.broadcast == "none" else

@@ -8,6 +8,7 @@
 // state.
 #include <hip/hip_runtime_api.h>
 
+#include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -289,7 +290,7 @@ int fork_to(kv_store* st, hipStream_t lane, int lane_index) {
         if (!st->list_forked) {
             KV_HIP(st, hipEventRecord(st->fork_ev, st->stream));
             st->list_forked = true;
-            st->lane_waited.assign(st->lanes.size(), 0);
+            std::fill(st->lane_waited.begin(), st->lane_waited.end(), (uint8_t)0);   // sized by kv_set_schedule
         }
         if (lane_index >= 0 && st->lane_waited[(size_t)lane_index]) return KV_OK;
         KV_HIP(st, hipStreamWaitEvent(lane, st->fork_ev, 0));
@@ -378,7 +379,12 @@ int pull_common(kv_store* st, int key, void* dst, int what) {
         return KV_ERR_STATE;
     }
     if (st->chain.marked[key]) {               // pushed, unit not launched yet: run after that launch
-        st->deferred[st->plan.key_unit[key]].push_back(Deferred{key, dst, what});
+        try {
+            st->deferred[st->plan.key_unit[key]].push_back(Deferred{key, dst, what});
+        } catch (const std::bad_alloc&) {
+            set_err(st->err, "out of host memory");
+            return KV_ERR_NOMEM;
+        }
         return KV_OK;
     }
     hipStream_t stream = key_stream(st, key);
@@ -570,7 +576,7 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
             st->row_valid[i].assign(st->plan.seg_key.size(), 0);
         }
         st->deferred.resize(st->plan.units.size());
-        st->log.reserve(64);
+        st->log.reserve(LOG_CAP);          // the launch path never allocates
     } catch (const std::bad_alloc&) {
         set_err(g_err, "kv_init: out of host memory");
         free_store(st);
@@ -870,6 +876,7 @@ int kv_set_schedule(kv_store* store, int schedule, int n_streams, int outstandin
                 KV_HIP(store, hipStreamCreateWithFlags(&l, hipStreamNonBlocking));     // default priority
                 store->lanes.push_back(l);
             }
+            store->lane_waited.assign((size_t)n_streams, 0);
         } catch (const std::bad_alloc&) {
             return KV_ERR_NOMEM;
         }
@@ -877,6 +884,7 @@ int kv_set_schedule(kv_store* store, int schedule, int n_streams, int outstandin
             (void)hipStreamDestroy(store->lanes.back());
             store->lanes.pop_back();
         }
+        store->lane_waited.resize(store->lanes.size());
         store->outstanding = outstanding;
     } else {
         store->outstanding = 0;
