@@ -41,6 +41,7 @@ def parse_args():
                     help="CPU work per oracle leg (single thread, all cores); whole steps are run until it is used up")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="N",
                     help="also launch the plain copy kernel N times on 1 GiB (byte-counter calibration)")
+    ap.add_argument("--ceilings", action="store_true", help="also measure the plain copy kernel on 1 GiB (context)")
     ap.add_argument("--pull-copy", action="store_true", help="also time a copying pull of every key (reported apart)")
     ap.add_argument("--schedule", choices=["chained", "funnel", "concurrent"], default="chained",
                     help="chained = one merged launch per step (headline); funnel / concurrent = one launch per key")
@@ -316,6 +317,31 @@ def main() -> int:
             store.pull_list(keys, outs)
         store.wait()
         extra["pull_list_all_keys_ms"] = (time.perf_counter() - t1) * 1e3 / 20
+
+    props = torch.cuda.get_device_properties(0)
+    device = {"name": props.name, "compute_units": props.multi_processor_count,
+              "memory_GiB": round(props.total_memory / 2 ** 30, 1)}
+    clk, width = getattr(props, "memory_clock_rate", None), getattr(props, "memory_bus_width", None)
+    if clk and width:
+        device["memory_clock_kHz"] = clk
+        device["memory_bus_bits"] = width
+        device["clock_x_width_x2_GBps"] = round(clk * 1e3 * width / 8 * 2 / 1e9, 1)     # double data rate
+    extra["device"] = device
+    if args.ceilings:
+        # plain copy kernel on 1 GiB as a measured ceiling for context (2 GiB of traffic per launch)
+        nb = 1 << 30
+        a = torch.empty(nb, dtype=torch.uint8, device="cuda")
+        b = torch.empty(nb, dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            kv.copy_bytes(b, a, nb)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            kv.copy_bytes(b, a, nb)
+        e1.record()
+        torch.cuda.synchronize()
+        extra["copy_kernel_ceiling_GBps"] = round(2 * nb * 20 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+        del a, b
 
     if args.calib_copy > 0:
         nb = 1 << 30

@@ -21,7 +21,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 __global__ void __launch_bounds__(KV_THREADS) kv_copy_kernel(f32x4* __restrict__ dst, const f32x4* __restrict__ src, size_t nvec) {
     const size_t stride = (size_t)gridDim.x * KV_THREADS;
-    for (size_t i = (size_t)blockIdx.x * KV_THREADS + threadIdx.x; i < nvec; i += stride) dst[i] = src[i];
+    for (size_t i = (size_t)blockIdx.x * KV_THREADS + threadIdx.x; i < nvec; i += stride)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 // Stand-in for a compute-bound backward operator: every lane first runs `spin` dependent
 // multiply-adds (no memory traffic), then copies its share.  The spun value can never equal
@@ -79,8 +80,8 @@ hipError_t kv_launch_busy_copy(void* dst, const void* src, size_t bytes, int spi
 hipError_t kv_launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream) {
     const size_t nvec = bytes / 16;
     if (nvec == 0) return hipSuccess;
-    size_t blocks = (nvec + KV_THREADS - 1) / KV_THREADS;
-    if (blocks > 256u * 16u) blocks = 256u * 16u;
+    size_t blocks = (nvec + KV_THREADS - 1) / KV_THREADS;      // one vector per lane: the fastest shape measured
+    if (blocks > (1u << 22)) blocks = 1u << 22;
     hipLaunchKernelGGL(kv_copy_kernel, dim3((unsigned)blocks), dim3(KV_THREADS), 0, stream,
                        static_cast<f32x4*>(dst), static_cast<const f32x4*>(src), nvec);
     return hipGetLastError();
