@@ -103,7 +103,7 @@ typedef struct kv_sgd_params {
 
 /*
  * Launch tuning; pass NULL for defaults.  None of these changes any result bit.
- *   unroll            16-byte vectors per thread per rank in one tile: 1, 2 or 4 (0 = default)
+ *   unroll            4-element vectors per thread per rank in one tile: 1, 2 or 4 (0 = default)
  *   workgroups_per_cu cap of resident workgroups per compute unit for the grid-stride
  *                     loop over tiles; 0 = one workgroup per tile
  *   nontemporal       cache policy: bit 0 = gradient loads carry the non-temporal hint; plus the policy
@@ -186,7 +186,8 @@ int kv_set_lr(kv_store* store, float lr);                      /* takes effect a
  * kv_push: hands over the W gradient copies of one key (KVStore push; it
  * "aggregates all the gradients of the same key").  dev_grads: host array of W
  * device pointers, each to numel elements of the gradient dtype, aligned at least
- * to the element size (16-byte alignment of all W selects the 128-bit path).
+ * to the element size (all W aligned to 16 bytes for fp32, 8 bytes for fp16, selects the
+ * vector path).
  * The gradients are read in place, asynchronously: they must stay valid and
  * unmodified until kv_wait returns or the stream is synchronised.  Never blocks.
  * When the push completes the next unit in order, that unit and every directly
@@ -224,7 +225,8 @@ int kv_weights_ptr(kv_store* store, int key, void** dev_ptr_out);
  * tensor), fused into the update: from the next launch on, the kernel that computes the key's new
  * weights also writes them to n_replicas caller-owned device buffers of numel elements each, as
  * fp32 (dtype KV_F32) or rounded to nearest-even fp16 (KV_F16).  dev_dst: host array of n_replicas
- * device pointers, aligned to the element (16-byte alignment of all of them keeps the 128-bit path).
+ * device pointers, aligned to the element (all of them aligned to 16 bytes for fp32 replicas, 8 bytes
+ * for fp16 replicas, keeps the vector path).
  * Every key of a store must use the same n_replicas and dtype (KV_ERR_STATE otherwise); n_replicas = 0
  * removes the key's replicas.  Blocks until the store's streams are idle.  The replicas must stay
  * valid while pushes of the key can still launch.

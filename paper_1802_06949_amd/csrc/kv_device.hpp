@@ -41,5 +41,6 @@ struct KvKernelSel {
     int nontemporal;
 };
 
-// Elements per tile for a gradient dtype and unroll factor.
-constexpr int kv_tile_elems(int grad_f16, int unroll) { return KV_THREADS * (grad_f16 ? 8 : 4) * unroll; }
+// Elements per tile: every lane owns 4 consecutive elements per unrolled vector, whatever the
+// gradient dtype.
+constexpr int kv_tile_elems(int /*grad_f16*/, int unroll) { return KV_THREADS * 4 * unroll; }

@@ -7,9 +7,9 @@
 // The path is a pure streaming pass: per parameter element it reads W gradient
 // values once, reads w and m, and writes w' and m'.  There is no reuse, so there
 // is no LDS staging and no MFMA; what matters is that every lane issues
-// independent 128-bit loads (all W ranks, and `U` vectors per rank, are in flight
-// before the first add) and that a wavefront's 64 lanes cover 1 KiB of contiguous
-// memory per load instruction.
+// independent vector loads (128 bits of fp32 or 64 bits of fp16 gradients per rank; all W
+// ranks, and `U` vectors per rank, are in flight before the first add) and that a
+// wavefront's 64 lanes cover contiguous memory per load instruction.
 //
 // Arithmetic contract (must match bit for bit what the header of the C ABI
 // states): each element is owned by one lane for all W ranks, the ranks are
@@ -31,7 +31,7 @@
 namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 template <bool F16> struct Grad;
 template <> struct Grad<false> {
@@ -43,13 +43,17 @@ template <> struct Grad<false> {
     }
     static __device__ __forceinline__ float widen1(elem e) { return e; }
 };
+// Half-precision gradients are read 8 bytes (4 values) per lane, not 16: a lane then owns 4
+// consecutive elements, exactly one 16-byte vector of w and of m, so that every load and store of
+// the fp32 state covers whole cache lines.  (With 8 halves per lane the state accesses of a
+// wavefront touch every line half, twice; measured 9 % slower on ResNet-50 W=32.)
 template <> struct Grad<true> {
     using elem = _Float16;
-    using vec = f16x8;
-    static constexpr int VEC = 8;
-    static __device__ __forceinline__ void widen(const vec& v, float (&o)[8]) {
+    using vec = f16x4;
+    static constexpr int VEC = 4;
+    static __device__ __forceinline__ void widen(const vec& v, float (&o)[4]) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) o[i] = (float)v[i];      // exact: every binary16 value is a binary32 value
+        for (int i = 0; i < 4; ++i) o[i] = (float)v[i];      // exact: every binary16 value is a binary32 value
     }
     static __device__ __forceinline__ float widen1(elem e) { return (float)e; }
 };
@@ -245,8 +249,6 @@ struct Bcast {
     int f16;
 };
 
-typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
-
 __device__ __forceinline__ void bcast4(const Bcast& b, int64_t e, const f32x4& wn) {
     if (b.n == 0) return;
     if (b.f16) {
@@ -365,8 +367,11 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
             }
         }
 
+        // The vector path needs every gradient pointer aligned to one gradient vector (16 bytes of
+        // fp32, 8 bytes of fp16) and every replica pointer to one replica vector (16 or 8 bytes).
         uint64_t bits = 0;
         for (int r = 0; r < W; ++r) bits |= gp[r];
+        bool vec_ok = (bits & (uint64_t)(NV * sizeof(E) - 1)) == 0;
 
         Bcast bc{nullptr, 0, a.bcast_f16};
         if (a.bcast_n > 0) {
@@ -374,10 +379,11 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
             if (row[0] != 0) {
                 bc.row = row;
                 bc.n = a.bcast_n;
-                for (int r = 0; r < a.bcast_n; ++r) bits |= row[r];
+                uint64_t rbits = 0;
+                for (int r = 0; r < a.bcast_n; ++r) rbits |= row[r];
+                vec_ok = vec_ok && (rbits & (a.bcast_f16 ? 7u : 15u)) == 0;
             }
         }
-        const bool vec_ok = (bits & 15u) == 0;      // every gradient and replica buffer 16-byte aligned
 
         if (vec_ok && full) {
             // every gradient load of every unrolled vector is issued before the first store

@@ -531,11 +531,10 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
 
     // Defaults from sweeps on MI355X.  Non-temporal gradient loads keep the streamed gradients
     // from evicting w and m out of the memory-side cache; giving every XCD blocks of 64 consecutive
-    // tiles and (for fp32 gradients) write-through stores of w', m' are worth a few percent each.
-    const bool f16 = grad_dtype == KV_F16;
+    // tiles and write-through stores of w', m' are worth a few percent each.
     st->unroll = 1;
     st->wg_per_cu = 0;
-    st->nontemporal = f16 ? 1 : 9;
+    st->nontemporal = 9;
     st->xcd_remap = 64;
     if (tuning) {
         if (tuning->unroll != 0) st->unroll = tuning->unroll;

@@ -35,7 +35,7 @@ def _grads(numel, W, dtype, seed, scale=0.01):
 
 
 # Lengths that straddle the vector width, the wavefront, the workgroup and the
-# tile sizes (1024 / 2048 / 4096 fp32, 2048 / 4096 / 8192 fp16), plus empty keys.
+# tile sizes (1024 / 2048 / 4096 elements for unroll 1 / 2 / 4), plus empty keys.
 RAGGED = [0, 1, 2, 3, 4, 5, 7, 8, 9, 63, 64, 65, 255, 256, 257, 1023, 1024, 1025, 2047, 2048, 2049,
           4095, 4096, 4097, 8191, 8192, 8193, 0, 12289, 20000]
 
@@ -149,7 +149,7 @@ def test_tuning_never_changes_a_bit(dtype, unroll, tuning):
         pair.close()
 
 
-@pytest.mark.parametrize("dtype,misalign", [("f32", 1), ("f32", 3), ("f16", 1), ("f16", 4), ("f16", 7)])
+@pytest.mark.parametrize("dtype,misalign", [("f32", 1), ("f32", 2), ("f32", 3), ("f16", 1), ("f16", 2), ("f16", 4), ("f16", 7)])
 def test_gradient_buffers_not_16_byte_aligned(dtype, misalign):
     """Views into a flat buffer: aligned to the element only, so the single-element path runs."""
     numel = [5, 1000, 4096, 9001]
