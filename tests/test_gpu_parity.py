@@ -536,3 +536,52 @@ def test_random_sessions_of_pushes_and_pulls(seed):
         pair.compare(f"random session {seed}")
     finally:
         pair.close()
+
+
+def test_maximum_rank_count_and_many_keys():
+    """W = 256 (the library's maximum) through the run-time-W kernel, and a store of 3000 small keys."""
+    numel = [5, 1030, 64]
+    for order in (orc.SEQUENTIAL, orc.PAIRWISE):
+        pair = Pair(numel, 256, "f16", 4096, lr=0.1, momentum=0.9, wd=1e-4, order=order)
+        try:
+            pair.set_weights([_rng(11, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+            pair.step(_grads(numel, 256, "f16", 1100))
+            pair.compare(f"W=256 order {order}")
+        finally:
+            pair.close()
+    r = _rng(12)
+    numel = [int(x) for x in r.integers(0, 300, size=3000)]
+    pair = Pair(numel, 2, "f32", 8192, lr=0.1, momentum=0.9, wd=1e-4, keep_sum=False)
+    try:
+        assert pair.gpu.plan.num_units > 50
+        g = [[(_rng(13, k, rr).standard_normal(n, dtype=F) * F(0.01)) for rr in range(2)] for k, n in enumerate(numel)]
+        import torch
+        flat = [torch.from_numpy(np.concatenate([gk[rr] for gk in g])).cuda() for rr in range(2)]
+        offs = np.concatenate([[0], np.cumsum(numel)])
+        dev = [[flat[rr][offs[k]:offs[k + 1]] for rr in range(2)] for k in range(len(numel))]   # views, mostly misaligned
+        pair.step(g, dev=dev)
+        pair.step(g, dev=dev, mode="each", order=[int(x) for x in r.permutation(len(numel))])
+        import torch
+        outs = [torch.empty(n, device="cuda") for n in numel]
+        pair.gpu.pull_list(list(range(len(numel))), outs)
+        pair.gpu.wait()
+        for k in range(len(numel)):
+            assert np.array_equal(outs[k].cpu().numpy().view(np.uint32), pair.cpu.w[k].view(np.uint32)), k
+    finally:
+        pair.close()
+
+
+def test_init_rejects_bad_arguments():
+    kv = pytest.importorskip("paper_1802_06949_amd")
+    for kwargs in (dict(W=0), dict(W=257), dict(reduce_order=2), dict(unroll=3), dict(nontemporal=2)):
+        args = dict(W=2, lr=0.1)
+        args.update(kwargs)
+        with pytest.raises(kv.KVError) as e:
+            kv.KVStore([10, 20], args.pop("W"), "f32", 4096, **args)
+        assert e.value.status == -1, kwargs
+    with pytest.raises(kv.KVError):
+        kv.KVStore([], 2, "f32", 4096, lr=0.1)
+    with pytest.raises(kv.KVError):
+        kv.KVStore([10, -5], 2, "f32", 4096, lr=0.1)
+    with pytest.raises(kv.KVError):
+        kv.KVStore([10], 2, "f32", 0, lr=0.1)
