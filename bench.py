@@ -328,20 +328,27 @@ def main() -> int:
         device["clock_x_width_x2_GBps"] = round(clk * 1e3 * width / 8 * 2 / 1e9, 1)     # double data rate
     extra["device"] = device
     if args.ceilings:
-        # plain copy kernel on 1 GiB as a measured ceiling for context (2 GiB of traffic per launch)
-        nb = 1 << 30
-        a = torch.empty(nb, dtype=torch.uint8, device="cuda")
-        b = torch.empty(nb, dtype=torch.uint8, device="cuda")
-        for _ in range(3):
-            kv.copy_bytes(b, a, nb)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(20):
-            kv.copy_bytes(b, a, nb)
-        e1.record()
-        torch.cuda.synchronize()
-        extra["copy_kernel_ceiling_GBps"] = round(2 * nb * 20 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
-        del a, b
+        # plain read and copy kernels on 1 GiB buffers (and on 96 MiB ones, which fit the memory-side
+        # cache) as measured ceilings for context
+        def rate(fn, nbytes_moved, reps=20):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return round(nbytes_moved * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+
+        ceil = {}
+        for label, nb in (("1GiB", 1 << 30), ("96MiB", 96 << 20)):
+            a = torch.zeros(nb, dtype=torch.uint8, device="cuda")
+            b = torch.zeros(nb, dtype=torch.uint8, device="cuda")
+            ceil[f"read_{label}_GBps"] = rate(lambda: kv.read_bytes(a, nb), nb)
+            ceil[f"copy_{label}_GBps"] = rate(lambda: kv.copy_bytes(b, a, nb), 2 * nb)
+            del a, b
+        extra["ceilings"] = ceil
 
     if args.calib_copy > 0:
         nb = 1 << 30

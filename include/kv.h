@@ -281,6 +281,10 @@ int kv_timing_intervals(kv_store* store, float* ms_out, int cap);
  * both pointers 16-byte aligned) on hip_stream: the known-size kernel against which
  * hardware byte counters are calibrated. */
 int kv_copy_bytes(void* dev_dst, const void* dev_src, size_t bytes, void* hip_stream);
+/* Plain streaming read kernel: reads `bytes` bytes (multiple of 16, pointer 16-byte aligned) and
+ * writes nothing.  With kv_copy_bytes it gives the measured read and copy ceilings of the GPU that the
+ * fused kernel's rate is put next to. */
+int kv_read_bytes(const void* dev_src, size_t bytes, void* hip_stream);
 
 /* Message for the last failure on this store (or, with NULL, of the last failed
  * kv_init / kv_plan_create / kv_chain_create on this thread).  Never NULL. */

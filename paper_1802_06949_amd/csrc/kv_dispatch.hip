@@ -24,6 +24,16 @@ __global__ void __launch_bounds__(KV_THREADS) kv_copy_kernel(f32x4* __restrict__
     for (size_t i = (size_t)blockIdx.x * KV_THREADS + threadIdx.x; i < nvec; i += stride)
         __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
+// Reads `nvec` 16-byte vectors with the non-temporal hint and writes nothing: the sum can never
+// equal the sentinel, but the compiler cannot know that.
+__global__ void __launch_bounds__(KV_THREADS) kv_read_kernel(const f32x4* __restrict__ src, size_t nvec, f32x4* sink) {
+    f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    const size_t stride = (size_t)gridDim.x * KV_THREADS;
+    for (size_t i = (size_t)blockIdx.x * KV_THREADS + threadIdx.x; i < nvec; i += stride)
+        acc += __builtin_nontemporal_load(src + i);
+    if (acc.x == -12345.678f && acc.y == 3.25f) sink[0] = acc;
+}
+
 // Stand-in for a compute-bound backward operator: every lane first runs `spin` dependent
 // multiply-adds (no memory traffic), then copies its share.  The spun value can never equal
 // the sentinel, but the compiler cannot know that, so the loop stays.
@@ -64,6 +74,16 @@ hipError_t kv_launch_gather(const KvTile* tiles, int64_t tile_lo, int64_t tile_h
     if (tile_hi <= tile_lo) return hipSuccess;
     hipLaunchKernelGGL(kv_gather_kernel, dim3((unsigned)(tile_hi - tile_lo)), dim3(KV_THREADS), 0, stream, tiles, tile_lo,
                        arena, dst_table);
+    return hipGetLastError();
+}
+
+hipError_t kv_launch_read(const void* src, size_t bytes, hipStream_t stream) {
+    const size_t nvec = bytes / 16;
+    if (nvec == 0) return hipSuccess;
+    size_t blocks = (nvec + KV_THREADS - 1) / KV_THREADS;
+    if (blocks > (1u << 22)) blocks = 1u << 22;
+    hipLaunchKernelGGL(kv_read_kernel, dim3((unsigned)blocks), dim3(KV_THREADS), 0, stream,
+                       static_cast<const f32x4*>(src), nvec, const_cast<f32x4*>(static_cast<const f32x4*>(src)));
     return hipGetLastError();
 }
 

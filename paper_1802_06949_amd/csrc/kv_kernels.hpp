@@ -27,3 +27,6 @@ hipError_t kv_launch_busy_copy(void* dst, const void* src, size_t bytes, int spi
 // table of one destination pointer per segment), one workgroup per tile.
 hipError_t kv_launch_gather(const KvTile* tiles, int64_t tile_lo, int64_t tile_hi, const float* arena,
                             float* const* dst_table, hipStream_t stream);
+
+// Reads `bytes` bytes (multiple of 16) and writes nothing: a measured ceiling for reads.
+hipError_t kv_launch_read(const void* src, size_t bytes, hipStream_t stream);

@@ -986,6 +986,19 @@ int kv_copy_bytes(void* dev_dst, const void* dev_src, size_t bytes, void* hip_st
     return KV_OK;
 }
 
+int kv_read_bytes(const void* dev_src, size_t bytes, void* hip_stream) {
+    if (!dev_src || (bytes & 15u) || ((uintptr_t)dev_src & 15u)) {
+        set_err(g_err, "kv_read_bytes: pointer and size must be multiples of 16");
+        return KV_ERR_ARG;
+    }
+    hipError_t e = kv_launch_read(dev_src, bytes, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) {
+        set_err(g_err, "kv_read_bytes: %s", hipGetErrorString(e));
+        return KV_ERR_HIP;
+    }
+    return KV_OK;
+}
+
 const char* kv_last_error(const kv_store* store) { return store ? store->err.c_str() : g_err.c_str(); }
 
 }  // extern "C"

@@ -96,6 +96,7 @@ def load_library() -> ctypes.CDLL:
     sig("kv_timing_mark", c_int, c_vp)
     sig("kv_timing_intervals", c_int, c_vp, P(ctypes.c_float), c_int)
     sig("kv_copy_bytes", c_int, c_vp, c_vp, c_sz, c_vp)
+    sig("kv_read_bytes", c_int, c_vp, c_sz, c_vp)
     sig("kv_last_error", ctypes.c_char_p, c_vp)
     _lib = L
     return L
@@ -382,5 +383,16 @@ def copy_bytes(dst, src, nbytes: int, stream: Optional[int] = None) -> None:
         stream = torch.cuda.current_stream().cuda_stream
     rc = L.kv_copy_bytes(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()), int(nbytes),
                          ctypes.c_void_p(int(stream)))
+    if rc != 0:
+        raise KVError(rc, _global_error(L))
+
+
+def read_bytes(src, nbytes: int, stream: Optional[int] = None) -> None:
+    """kv_read_bytes: the plain streaming read kernel (a measured ceiling for reads)."""
+    L = load_library()
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    rc = L.kv_read_bytes(ctypes.c_void_p(src.data_ptr()), int(nbytes), ctypes.c_void_p(int(stream)))
     if rc != 0:
         raise KVError(rc, _global_error(L))
