@@ -181,6 +181,10 @@ void kv_destroy(kv_store* store);                              /* drains the str
 int kv_set_weights (kv_store* store, int key, const void* src_f32);
 int kv_set_momentum(kv_store* store, int key, const void* src_f32);
 int kv_set_lr(kv_store* store, float lr);                      /* takes effect at the next launch */
+/* All optimizer parameters at once (same rules as at kv_init; they take effect at the next launch),
+ * and the ones in force; params_out->rescale is the resolved factor (1/W if it was given as <= 0). */
+int kv_set_sgd_params(kv_store* store, const kv_sgd_params* params /* host */);
+int kv_get_sgd_params(const kv_store* store, kv_sgd_params* params_out /* host */);
 
 /*
  * kv_push: hands over the W gradient copies of one key (KVStore push; it

@@ -630,6 +630,24 @@ int kv_set_lr(kv_store* store, float lr) {
     return KV_OK;
 }
 
+int kv_set_sgd_params(kv_store* store, const kv_sgd_params* params) {
+    if (!store || !params) return KV_ERR_ARG;
+    if (params->reduce_order != KV_REDUCE_SEQUENTIAL && params->reduce_order != KV_REDUCE_PAIRWISE) {
+        set_err(store->err, "kv_set_sgd_params: reduce_order %d unknown", params->reduce_order);
+        return KV_ERR_ARG;
+    }
+    store->p = *params;
+    store->rescale = params->rescale > 0.0f ? params->rescale : 1.0f / (float)store->W;
+    return KV_OK;
+}
+
+int kv_get_sgd_params(const kv_store* store, kv_sgd_params* params_out) {
+    if (!store || !params_out) return KV_ERR_ARG;
+    *params_out = store->p;
+    params_out->rescale = store->rescale;
+    return KV_OK;
+}
+
 int kv_push(kv_store* store, int key, const void* const* dev_grads) {
     if (!store) return KV_ERR_ARG;
     int rc = check_key(store, key);

@@ -78,6 +78,8 @@ def load_library() -> ctypes.CDLL:
     sig("kv_set_weights", c_int, c_vp, c_int, c_vp)
     sig("kv_set_momentum", c_int, c_vp, c_int, c_vp)
     sig("kv_set_lr", c_int, c_vp, ctypes.c_float)
+    sig("kv_set_sgd_params", c_int, c_vp, P(_SgdParams))
+    sig("kv_get_sgd_params", c_int, c_vp, P(_SgdParams))
     sig("kv_push", c_int, c_vp, c_int, P(c_vp))
     sig("kv_push_list", c_int, c_vp, c_int, P(c_int), P(c_vp))
     sig("kv_pull", c_int, c_vp, c_int, c_vp)
@@ -283,6 +285,16 @@ class KVStore:
 
     def set_lr(self, lr: float) -> None:
         self._check(self._L.kv_set_lr(self._h, lr))
+
+    def set_sgd_params(self, *, lr: float, momentum: float, wd: float, rescale: float = 0.0,
+                       reduce_order: int = KV_REDUCE_SEQUENTIAL) -> None:
+        p = _SgdParams(lr, momentum, wd, rescale, reduce_order)
+        self._check(self._L.kv_set_sgd_params(self._h, ctypes.byref(p)))
+
+    def get_sgd_params(self) -> dict:
+        p = _SgdParams()
+        self._check(self._L.kv_get_sgd_params(self._h, ctypes.byref(p)))
+        return dict(lr=p.lr, momentum=p.momentum, wd=p.wd, rescale=p.rescale, reduce_order=p.reduce_order)
 
     # --- push
     def push(self, key: int, grads: Sequence) -> None:

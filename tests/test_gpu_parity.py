@@ -447,6 +447,28 @@ def test_learning_rate_change_and_checkpoint_round_trip():
             b.close()
 
 
+def test_optimizer_parameters_can_change_between_steps():
+    numel = [100, 3000, 17]
+    W = 4
+    pair = Pair(numel, W, "f32", 4096, lr=0.1, momentum=0.0, wd=0.0)
+    try:
+        pair.set_weights([_rng(14, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        assert pair.gpu.get_sgd_params()["rescale"] == 0.25
+        for t, (lr, mu, wd, rs, order) in enumerate([(0.1, 0.0, 0.0, 0.0, 0), (0.05, 0.9, 1e-3, 0.0, 1),
+                                                      (0.2, 0.5, 0.0, 1.0, 0), (0.0, 0.9, 1e-2, 0.125, 1)]):
+            pair.gpu.set_sgd_params(lr=lr, momentum=mu, wd=wd, rescale=rs, reduce_order=order)
+            pair.cpu.lr, pair.cpu.momentum, pair.cpu.wd, pair.cpu.order = lr, mu, wd, order
+            pair.cpu.rescale = rs if rs > 0 else float(F(1) / F(W))
+            got = pair.gpu.get_sgd_params()
+            assert got["reduce_order"] == order and got["rescale"] == F(pair.cpu.rescale)
+            pair.step(_grads(numel, W, "f32", 1200 + t))
+            pair.compare(f"parameters {t}")
+        with pytest.raises(pair.kv.KVError):
+            pair.gpu.set_sgd_params(lr=0.1, momentum=0.0, wd=0.0, reduce_order=5)
+    finally:
+        pair.close()
+
+
 def test_zero_copy_weights_pointer_and_timing():
     import ctypes
     import torch
