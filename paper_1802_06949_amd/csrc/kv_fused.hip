@@ -60,7 +60,7 @@ template <> struct Grad<true> {
 
 // Cache-policy mask of a kernel instantiation:
 //   bit 0       gradient loads carry the non-temporal hint
-//   bit 1       loads of w and m carry it
+//   bit 1       loads of w and m carry it (measured slower; not instantiated)
 //   bits 2..3   stores of w', m' (and s): 0 = plain, 4 = non-temporal, 8 = agent scope (write through L2)
 template <bool NT, typename T>
 __device__ __forceinline__ T load_grad(const T* p) {
@@ -75,7 +75,8 @@ __device__ __forceinline__ f32x4 load_state(const float* p) {
 // Stores 16 bytes at element `k` of the uniform base pointer `base`.  Policy 8 uses a raw
 // buffer store, whose cache-policy operand can carry the sc1 bit (write through L2 to memory
 // at once instead of leaving a dirty line in L2); the buffer descriptor spans exactly the
-// bytes handed in, so an out-of-range lane could not write.
+// bytes handed in, so an out-of-range lane could not write.  0x00020000 is word 3 of a raw
+// (untyped, 32-bit data format) buffer descriptor on gfx9-family targets.
 template <int POL>
 __device__ __forceinline__ void store_state(float* base, int k, unsigned span_bytes, const f32x4& v) {
     if constexpr (POL == 4) {
