@@ -107,8 +107,9 @@ typedef struct kv_sgd_params {
  *   workgroups_per_cu cap of resident workgroups per compute unit for the grid-stride
  *                     loop over tiles; 0 = one workgroup per tile
  *   nontemporal       cache policy: bit 0 = gradient loads carry the non-temporal hint; plus the policy
- *                     of the stores of w', m' (and s): 0 = plain, 4 = non-temporal, 8 = write through L2;
- *                     one of 0, 1, 5, 9; -1 = default
+ *                     of the stores of w', m' (and s): 0 = plain, 4 = non-temporal, 8 = write through L2,
+ *                     12 = write through L2 and non-temporal; one of 0, 1, 5, 9, 13; -1 = default (9 if
+ *                     w and m together fit the 256 MiB memory-side cache, else 13)
  *   xcd_remap         how tiles are dealt to the 8 XCDs: 0 = one by one, round robin; 1 = eight contiguous
  *                     ranges, one per XCD; G > 1 = blocks of G consecutive tiles per XCD; -1 = default
  */

@@ -61,7 +61,8 @@ template <> struct Grad<true> {
 // Cache-policy mask of a kernel instantiation:
 //   bit 0       gradient loads carry the non-temporal hint
 //   bit 1       loads of w and m carry it (measured slower; not instantiated)
-//   bits 2..3   stores of w', m' (and s): 0 = plain, 4 = non-temporal, 8 = agent scope (write through L2)
+//   bits 2..3   stores of w', m' (and s): 0 = plain, 4 = non-temporal, 8 = agent scope (write through L2),
+//               12 = both
 template <bool NT, typename T>
 __device__ __forceinline__ T load_grad(const T* p) {
     if constexpr (NT) return __builtin_nontemporal_load(p);
@@ -81,10 +82,11 @@ template <int POL>
 __device__ __forceinline__ void store_state(float* base, int k, unsigned span_bytes, const f32x4& v) {
     if constexpr (POL == 4) {
         __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(base + k));
-    } else if constexpr (POL == 8) {
+    } else if constexpr (POL == 8 || POL == 12) {
         typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(base, 0, span_bytes, 0x00020000);
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rsrc, k * 4, 0, /*sc1*/ 16);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rsrc, k * 4, 0,
+                                               POL == 12 ? /*sc1 + nt*/ 18 : /*sc1*/ 16);
     } else {
         *reinterpret_cast<f32x4*>(base + k) = v;
     }
@@ -442,6 +444,7 @@ hipError_t pick_nt(const KvKernelSel& s, const KvLaunchArgs& a, unsigned grid, h
         case 1: return launch_one<F16, WT, PAIRWISE, KEEP, U, 1>(a, grid, st);
         case 5: return launch_one<F16, WT, PAIRWISE, KEEP, U, 5>(a, grid, st);
         case 9: return launch_one<F16, WT, PAIRWISE, KEEP, U, 9>(a, grid, st);
+        case 13: return launch_one<F16, WT, PAIRWISE, KEEP, U, 13>(a, grid, st);
         default: return hipErrorInvalidValue;
     }
 }

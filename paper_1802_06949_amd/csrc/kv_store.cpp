@@ -532,9 +532,12 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     // Defaults from sweeps on MI355X.  Non-temporal gradient loads keep the streamed gradients
     // from evicting w and m out of the memory-side cache; giving every XCD blocks of 64 consecutive
     // tiles and write-through stores of w', m' are worth a few percent each.
+    // State (w and m) that fits the 256 MiB memory-side cache stays resident between iterations
+    // if its stores are left to allocate there; state that cannot fit is better streamed past it.
+    const int64_t state_bytes = 2 * st->plan.arena_numel * (int64_t)sizeof(float);
     st->unroll = 1;
     st->wg_per_cu = 0;
-    st->nontemporal = 9;
+    st->nontemporal = state_bytes > (256LL << 20) ? 13 : 9;
     st->xcd_remap = 64;
     if (tuning) {
         if (tuning->unroll != 0) st->unroll = tuning->unroll;
@@ -543,8 +546,8 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
         if (tuning->xcd_remap >= 0) st->xcd_remap = tuning->xcd_remap;
     }
     const int nt = st->nontemporal;
-    if ((st->unroll != 1 && st->unroll != 2 && st->unroll != 4) || !(nt == 0 || nt == 1 || nt == 5 || nt == 9)) {
-        set_err(g_err, "kv_init: tuning.unroll must be 1, 2 or 4 and tuning.nontemporal one of 0, 1, 5, 9");
+    if ((st->unroll != 1 && st->unroll != 2 && st->unroll != 4) || !(nt == 0 || nt == 1 || nt == 5 || nt == 9 || nt == 13)) {
+        set_err(g_err, "kv_init: tuning.unroll must be 1, 2 or 4 and tuning.nontemporal one of 0, 1, 5, 9, 13");
         delete st;
         return KV_ERR_ARG;
     }

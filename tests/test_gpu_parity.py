@@ -134,7 +134,7 @@ def test_ragged_keys_all_rank_counts(dtype, W, order):
 
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
 @pytest.mark.parametrize("unroll", [1, 2, 4])
-@pytest.mark.parametrize("tuning", [dict(), dict(workgroups_per_cu=1), dict(xcd_remap=0), dict(nontemporal=0), dict(nontemporal=1), dict(nontemporal=5), dict(nontemporal=9),
+@pytest.mark.parametrize("tuning", [dict(), dict(workgroups_per_cu=1), dict(xcd_remap=0), dict(nontemporal=0), dict(nontemporal=1), dict(nontemporal=5), dict(nontemporal=9), dict(nontemporal=13),
                                     dict(workgroups_per_cu=2, xcd_remap=1), dict(workgroups_per_cu=3, xcd_remap=0), dict(xcd_remap=1),
                                     dict(xcd_remap=7), dict(xcd_remap=3, workgroups_per_cu=1), dict(xcd_remap=4096)])
 def test_tuning_never_changes_a_bit(dtype, unroll, tuning):
