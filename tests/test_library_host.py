@@ -162,3 +162,20 @@ def test_init_fails_loudly_without_a_gpu():
     with pytest.raises(kv.KVError) as e:
         kv.KVStore([10, 20], 2, lr=0.1, stream=0)
     assert e.value.status == -6
+
+
+def test_headers_are_valid_c_and_cxx(tmp_path):
+    """The boundary is a C ABI: both headers must compile as C99 and as C++ on their own."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("needs gcc")
+    inc = os.path.join(ROOT, "include")
+    src = tmp_path / "use_headers.c"
+    src.write_text('#include "kv.h"\n#include "kv_engine.h"\n'
+                   "int use(kv_store* s, const void* const* g) { kv_sgd_params p = {0.1f, 0.9f, 1e-4f, 0.0f, KV_REDUCE_SEQUENTIAL};\n"
+                   "  (void)p; return kv_push(s, 0, g) + kv_wait(s, -1) + KV_SCHED_FUNNEL + KV_FLAG_DESCENDING; }\n")
+    for cmd in (["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only"],
+                ["g++", "-std=c++17", "-x", "c++", "-Wall", "-Wextra", "-Werror", "-fsyntax-only"]):
+        r = subprocess.run(cmd + ["-I", inc, str(src)], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
