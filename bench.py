@@ -35,6 +35,8 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..5 (3 = ResNet-50-shaped, W=8)")
+    ap.add_argument("--ranks", type=int, default=0, help="override the configuration's W (characterisation runs)")
+    ap.add_argument("--grad-dtype", choices=["f32", "f16"], default=None, help="override the gradient dtype")
     ap.add_argument("--sets", type=int, default=2, help="distinct gradient sets cycled through (fresh buffers each step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=8.0,
@@ -194,6 +196,10 @@ def main() -> int:
         return overlap_mode(args)
 
     cfg = wl.get_config(args.config)
+    if args.ranks or args.grad_dtype:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, W=args.ranks or cfg.W, grad_dtype=args.grad_dtype or cfg.grad_dtype,
+                                  name=f"{cfg.name}[W={args.ranks or cfg.W},{args.grad_dtype or cfg.grad_dtype}]")
     K = len(cfg.keys)
     N = cfg.total_numel
     itemsize = cfg.grad_itemsize
