@@ -255,33 +255,29 @@ def main() -> int:
     keys = list(range(K))
     lists = [store.make_push_list(keys, d) for d in dev_sets]
     if args.push_mode == "each":
+        # one kv_push per key, in key order, with the pointer arrays marshalled once
         import ctypes
-        W = cfg.W
-        rows = [[(ctypes.c_void_p * W)(*[int(t.data_ptr()) for t in d[k]]) for k in keys] for d in dev_sets]
-        push, h = store._L.kv_push, store._h
+        rows = [[(ctypes.c_void_p * cfg.W)(*[int(t.data_ptr()) for t in d[k]]) for k in keys] for d in dev_sets]
+        raw_push, handle = store._L.kv_push, store._h
 
-        class _Each:                                    # same call shape as push_list below
-            def __init__(self, r):
-                self.r = r
-
-        def push_each(pl):
-            for k, row in enumerate(pl.r):
-                rc = push(h, k, row)
+        def do_step(i):
+            for k, row in enumerate(rows[i % nsets]):
+                rc = raw_push(handle, k, row)
                 if rc != 0:
                     raise kv.KVError(rc, store.last_error())
-
-        lists = [_Each(r) for r in rows]
-        store.push_list = push_each
+    else:
+        def do_step(i):
+            store.push_list(lists[i % nsets])
 
     for i in range(args.warmup):
-        store.push_list(lists[i % nsets])
+        do_step(i)
     store.wait()
     torch.cuda.synchronize()
 
     store.timing_begin()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        store.push_list(lists[i % nsets])
+        do_step(i)
     store.wait()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -293,7 +289,7 @@ def main() -> int:
     if args.schedule == "chained":
         store.timing_begin()
         for i in range(min(args.steps, 500)):
-            store.push_list(lists[i % nsets])
+            do_step(i)
             store.timing_mark()
         store.wait()
         store.timing_end()
