@@ -49,6 +49,7 @@ def parse_args():
                     help="chained = one merged launch per step (headline); funnel / concurrent = one launch per key")
     ap.add_argument("--push-mode", choices=["list", "each"], default="list",
                     help="list = one kv_push_list per step (headline); each = one kv_push per key, in key order")
+    ap.add_argument("--lazy", action="store_true", help="KV_FLAG_LAZY_LAUNCH: single pushes merge into one launch")
     ap.add_argument("--streams", type=int, default=4, help="concurrent schedule: number of streams")
     ap.add_argument("--outstanding", type=int, default=0, help="concurrent schedule: barrier after this many keys")
     ap.add_argument("--broadcast", choices=["none", "f32", "f16"], default="none",
@@ -236,7 +237,7 @@ def main() -> int:
     t_gen = time.perf_counter() - t_gen
 
     store = kv.KVStore(cfg.numel, cfg.W, cfg.grad_dtype, cfg.bucket_bytes, lr=cfg.lr, momentum=cfg.momentum, wd=cfg.wd,
-                       keep_sum=False, unroll=args.unroll, workgroups_per_cu=args.workgroups_per_cu,
+                       keep_sum=False, lazy=args.lazy, unroll=args.unroll, workgroups_per_cu=args.workgroups_per_cu,
                        nontemporal=args.nontemporal, xcd_remap=args.xcd_remap)
     for k, w in enumerate(weights):
         if w.size:

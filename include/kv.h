@@ -62,10 +62,16 @@ enum kv_dtype { KV_F32 = 0, KV_F16 = 1 };                 /* gradient element ty
 enum kv_reduce_order { KV_REDUCE_SEQUENTIAL = 0,          /* s = g_0; s += g_r, r=1.. */
                        KV_REDUCE_PAIRWISE   = 1 };        /* balanced tree, see below */
 enum kv_flags { KV_FLAG_KEEP_SUM   = 1u,                  /* also store s (kv_pull_grad) */
-                KV_FLAG_DESCENDING = 2u };                /* units run from the last one down to unit 0: the
+                KV_FLAG_DESCENDING = 2u,                  /* units run from the last one down to unit 0: the
                                                              order in which a backward pass produces gradients
                                                              (last layer first).  Still a function of the key
                                                              set alone, so the same on every worker. */
+                KV_FLAG_LAZY_LAUNCH = 4u };               /* a single kv_push launches nothing until every key
+                                                             of the iteration is pushed (then all units go out
+                                                             as ONE launch), or until a pull, wait or barrier
+                                                             asks for what is ready: the paper's Dependency
+                                                             Chaining loop, which issues all pushes before the
+                                                             first pull */
 
 /*
  * The paper's three ways of embedding the aggregation into the worker's task flow

@@ -379,6 +379,10 @@ int pull_common(kv_store* st, int key, void* dst, int what) {
         set_err(st->err, "kv_pull_grad needs a store created with KV_FLAG_KEEP_SUM");
         return KV_ERR_STATE;
     }
+    if (st->chain.marked[key] && (st->flags & KV_FLAG_LAZY_LAUNCH)) {
+        rc = drain_chain(st);                  // a pull is a reason to launch what is ready
+        if (rc != KV_OK) return rc;
+    }
     if (st->chain.marked[key]) {               // pushed, unit not launched yet: run after that launch
         try {
             st->deferred[st->plan.key_unit[key]].push_back(Deferred{key, dst, what});
@@ -505,7 +509,7 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
         return KV_ERR_ARG;
     }
     *out = nullptr;
-    if (!params || W < 1 || W > KV_MAX_W || (flags & ~(unsigned)(KV_FLAG_KEEP_SUM | KV_FLAG_DESCENDING))) {
+    if (!params || W < 1 || W > KV_MAX_W || (flags & ~(unsigned)(KV_FLAG_KEEP_SUM | KV_FLAG_DESCENDING | KV_FLAG_LAZY_LAUNCH))) {
         set_err(g_err, "kv_init: bad arguments (params=%p, W=%d, flags=%u)", (const void*)params, W, flags);
         return KV_ERR_ARG;
     }
@@ -668,6 +672,8 @@ int kv_push(kv_store* store, int key, const void* const* dev_grads) {
         return rc;
     }
     record_grads(store, key, dev_grads);
+    // lazy stores let single pushes pile up until the whole iteration can go out as one launch
+    if ((store->flags & KV_FLAG_LAZY_LAUNCH) && store->chain.pending_keys < store->plan.num_keys) return KV_OK;
     return drain_chain(store);
 }
 
@@ -787,6 +793,10 @@ int kv_weights_ptr(kv_store* store, int key, void** dev_ptr_out) {
 
 int kv_wait(kv_store* store, int key) {
     if (!store) return KV_ERR_ARG;
+    if ((store->flags & KV_FLAG_LAZY_LAUNCH) && store->schedule == KV_SCHED_CHAINED) {
+        int rc = drain_chain(store);
+        if (rc != KV_OK) return rc;
+    }
     if (key >= 0) {
         int rc = check_key(store, key);
         if (rc != KV_OK) return rc;
@@ -872,7 +882,14 @@ int kv_wait_event(kv_store* store, void* hip_event) {
     return KV_OK;
 }
 
-int kv_barrier(kv_store* store) { return store ? barrier_all(store) : KV_ERR_ARG; }
+int kv_barrier(kv_store* store) {
+    if (!store) return KV_ERR_ARG;
+    if ((store->flags & KV_FLAG_LAZY_LAUNCH) && store->schedule == KV_SCHED_CHAINED) {
+        int rc = drain_chain(store);
+        if (rc != KV_OK) return rc;
+    }
+    return barrier_all(store);
+}
 
 int kv_set_schedule(kv_store* store, int schedule, int n_streams, int outstanding) {
     if (!store) return KV_ERR_ARG;

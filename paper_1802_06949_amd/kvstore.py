@@ -14,6 +14,7 @@ KV_F32, KV_F16 = 0, 1
 KV_REDUCE_SEQUENTIAL, KV_REDUCE_PAIRWISE = 0, 1
 KV_FLAG_KEEP_SUM = 1
 KV_FLAG_DESCENDING = 2
+KV_FLAG_LAZY_LAUNCH = 4
 KV_SCHED_CHAINED, KV_SCHED_FUNNEL, KV_SCHED_CONCURRENT = 0, 1, 2
 STATUS = {0: "KV_OK", -1: "KV_ERR_ARG", -2: "KV_ERR_KEY", -3: "KV_ERR_STATE", -4: "KV_ERR_ALIGN",
           -5: "KV_ERR_INCOMPLETE", -6: "KV_ERR_HIP", -7: "KV_ERR_NOMEM"}
@@ -236,7 +237,7 @@ class KVStore:
 
     def __init__(self, key_numel: Sequence[int], W: int, grad_dtype="f32", bucket_bytes: int = 1 << 22, *,
                  lr: float, momentum: float = 0.0, wd: float = 0.0, rescale: float = 0.0,
-                 reduce_order: int = KV_REDUCE_SEQUENTIAL, keep_sum: bool = False, descending: bool = False,
+                 reduce_order: int = KV_REDUCE_SEQUENTIAL, keep_sum: bool = False, descending: bool = False, lazy: bool = False,
                  stream: Optional[int] = None,
                  unroll: int = 0, workgroups_per_cu: int = -1, nontemporal: int = -1, xcd_remap: int = -1):
         self._L = load_library()
@@ -254,7 +255,8 @@ class KVStore:
         t = _Tuning(unroll, workgroups_per_cu, nontemporal, xcd_remap)
         h = ctypes.c_void_p()
         rc = self._L.kv_init(ctypes.byref(h), n, arr, self.grad_dtype, self.W, int(bucket_bytes), ctypes.byref(p),
-                             (KV_FLAG_KEEP_SUM if keep_sum else 0) | (KV_FLAG_DESCENDING if descending else 0),
+                             (KV_FLAG_KEEP_SUM if keep_sum else 0) | (KV_FLAG_DESCENDING if descending else 0) |
+                             (KV_FLAG_LAZY_LAUNCH if lazy else 0),
                              ctypes.byref(t), ctypes.c_void_p(self.stream))
         if rc != 0:
             raise KVError(rc, _global_error(self._L))

@@ -113,3 +113,39 @@ def test_concurrent_pull_then_barrier_sees_the_update():
             assert np.array_equal(outs[k].cpu().numpy(), pair.cpu.w[k])
     finally:
         pair.close()
+
+
+def test_lazy_store_merges_single_pushes_into_one_launch():
+    """The paper's Dependency Chaining loop: all pushes first, then the pulls.  With
+    KV_FLAG_LAZY_LAUNCH the single pushes pile up and the whole iteration is one launch."""
+    import torch
+    cfg = wl.get_config(2)
+    K = len(cfg.keys)
+    pair = Pair(cfg.numel, cfg.W, "f32", cfg.bucket_bytes, lr=cfg.lr, momentum=cfg.momentum, wd=cfg.wd, lazy=True)
+    try:
+        U = pair.gpu.plan.num_units
+        pair.set_weights(wl.make_weights(cfg))
+        for t in range(2):
+            pair.step(wl.make_step_gradients(cfg, t), mode="each", order=[int(x) for x in _rng(60 + t).permutation(K)])
+            pair.compare(f"lazy step {t}")
+        assert pair.gpu.launch_log()[1] == [(0, U)] * 2
+        # a pull in the middle of the pushes launches what is ready and is served after its key's update
+        g = wl.make_step_gradients(cfg, 2)
+        dev = pair.upload(g)
+        first_unit_keys = pair.gpu.plan.unit(0)[0]
+        for k in first_unit_keys:
+            pair.gpu.push(k, dev[k])
+        assert pair.gpu.launch_log()[0] == 2                   # nothing launched yet
+        out = torch.zeros(cfg.numel[first_unit_keys[0]], device="cuda")
+        pair.gpu.pull(first_unit_keys[0], out)
+        assert pair.gpu.launch_log()[1][-1] == (0, 1)          # unit 0 went out for the pull
+        for k in range(K):
+            if k not in first_unit_keys:
+                pair.gpu.push(k, dev[k])
+        pair.gpu.wait()
+        pair.cpu.step(g)
+        assert np.array_equal(out.cpu().numpy(), pair.cpu.w[first_unit_keys[0]])
+        pair.compare("lazy with a pull in the middle")
+        assert pair.gpu.launch_log()[1][-1] == (1, U - 1)
+    finally:
+        pair.close()
