@@ -184,7 +184,8 @@ void kv_destroy(kv_store* store);                              /* drains the str
 
 /* Initial value of a key (the paper broadcasts rank 0's value; here there is one
  * copy) and momentum restore.  src: numel fp32 values, device or host memory;
- * copied on the store's stream, in order with pushes and pulls. */
+ * copied on the store's stream (the one given to kv_init, under every schedule), in order with
+ * pushes and pulls of the key; src may be reused as soon as that stream's order allows. */
 int kv_set_weights (kv_store* store, int key, const void* src_f32);
 int kv_set_momentum(kv_store* store, int key, const void* src_f32);
 int kv_set_lr(kv_store* store, float lr);                      /* takes effect at the next launch */
@@ -261,9 +262,9 @@ int kv_wait(kv_store* store, int key);
  * kv_set_schedule: the paper's KVStore.create("type").  Allowed only between iterations
  * (KV_ERR_STATE while pushed keys wait); drains all streams first.  n_streams (1..KV_MAX_STREAMS)
  * and outstanding (>= 0) are read for KV_SCHED_CONCURRENT only; the extra streams are created by
- * the store at default priority.  In the concurrent schedule a key's launch, its pulls and its
- * sets run on the key's stream, ordered after everything issued earlier on the stream given to
- * kv_init; work the caller issues afterwards on that stream is ordered after a key only through
+ * the store at default priority.  In the concurrent schedule a key's launch and its pulls run on
+ * the key's stream, ordered after everything issued earlier on the stream given to kv_init (so
+ * gradients and pull destinations must stay valid until kv_wait(key) or kv_barrier); work the caller issues afterwards on that stream is ordered after a key only through
  * kv_wait(key) or kv_barrier.  In the launch log per-key launches appear as (key, 0).
  * kv_barrier: the paper's Kvstore.barrier: blocks until nothing launched so far is outstanding
  * on any stream.  Unlike kv_wait(-1) it does not report an incomplete iteration.

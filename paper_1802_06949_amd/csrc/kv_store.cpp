@@ -95,6 +95,7 @@ struct kv_store {
     int since_barrier = 0;
     std::vector<hipStream_t> lanes;               // concurrent schedule: one stream per "communicator"
     hipEvent_t fork_ev = nullptr;                 // orders a lane after the work already on the main stream
+    hipEvent_t join_ev = nullptr;                 // orders the main stream after a lane
     bool in_list = false;                         // inside kv_push_list: one fork event serves the whole list
     bool list_forked = false;
     std::vector<uint8_t> lane_waited;             // per lane: already waits for this list's fork event
@@ -138,6 +139,7 @@ void free_store(kv_store* st) {
         if (st->stage_ev[i]) (void)hipEventDestroy(st->stage_ev[i]);
     for (hipStream_t l : st->lanes) (void)hipStreamDestroy(l);
     if (st->fork_ev) (void)hipEventDestroy(st->fork_ev);
+    if (st->join_ev) (void)hipEventDestroy(st->join_ev);
     for (hipEvent_t e : st->marks) (void)hipEventDestroy(e);
     if (st->t0) (void)hipEventDestroy(st->t0);
     if (st->t1) (void)hipEventDestroy(st->t1);
@@ -408,11 +410,17 @@ int set_common(kv_store* st, int key, const void* src, float* arena) {
         set_err(st->err, "set of key %d: null source", key);
         return KV_ERR_ARG;
     }
-    hipStream_t stream = key_stream(st, key);
-    rc = fork_to(st, stream, lane_of(st, key));
-    if (rc != KV_OK) return rc;
+    // The copy always runs on the store's own stream, the one the caller's memory management knows
+    // about (a source buffer recycled right after this call must not be read later from another
+    // stream).  In the concurrent schedule the store's stream first waits for what the key's lane
+    // still has in flight; the key's next launch is ordered after the copy by its fork event.
+    hipStream_t lane = key_stream(st, key);
+    if (lane != st->stream) {
+        KV_HIP(st, hipEventRecord(st->join_ev, lane));
+        KV_HIP(st, hipStreamWaitEvent(st->stream, st->join_ev, 0));
+    }
     KV_HIP(st, hipMemcpyAsync(arena + st->plan.key_arena_off[key], src, (size_t)n * sizeof(float), hipMemcpyDefault,
-                              stream));
+                              st->stream));
     return KV_OK;
 }
 
@@ -608,6 +616,7 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     KV_INIT_HIP(hipHostMalloc((void**)&st->h_stage, (size_t)NSTAGE * st->table_elems * sizeof(void*), hipHostMallocDefault));
     for (int i = 0; i < NSTAGE; ++i) KV_INIT_HIP(hipEventCreateWithFlags(&st->stage_ev[i], hipEventDisableTiming));
     KV_INIT_HIP(hipEventCreateWithFlags(&st->fork_ev, hipEventDisableTiming));
+    KV_INIT_HIP(hipEventCreateWithFlags(&st->join_ev, hipEventDisableTiming));
     KV_INIT_HIP(hipEventCreate(&st->t0));
     KV_INIT_HIP(hipEventCreate(&st->t1));
     // the host vector `tiles` dies at return: wait for its upload
