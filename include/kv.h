@@ -195,8 +195,8 @@ int kv_set_sgd_params(kv_store* store, const kv_sgd_params* params /* host */);
 int kv_get_sgd_params(const kv_store* store, kv_sgd_params* params_out /* host */);
 
 /*
- * kv_push: hands over the W gradient copies of one key (KVStore push; it
- * "aggregates all the gradients of the same key").  dev_grads: host array of W
+ * kv_push: hands over the W gradient copies of one key (KVStore API section: a
+ * push sums every gradient that carries the same key).  dev_grads: host array of W
  * device pointers, each to numel elements of the gradient dtype, aligned at least
  * to the element size (all W aligned to 16 bytes for fp32, 8 bytes for fp16, selects the
  * vector path).

@@ -15,8 +15,8 @@
  *                                                    paper's collective is an
  *                                                    elementwise MPI_SUM of
  *                                                    MPI_FLOAT, i.e. fp32
- *   ghat  = rescale * s                              "multiplied by a scaling
- *                                                    factor"
+ *   ghat  = rescale * s                              the aggregate times a
+ *                                                    scale factor
  *   t     = ghat + wd * w[i]                         L2 weight decay (extension)
  *   dw    = momentum * m[i] - lr * t                 eq. (1): dw = -eta * g,
  *                                                    extended by momentum
@@ -36,9 +36,11 @@
  *                   h = largest power of two strictly below n.
  *
  * Parity pins: tests/test_oracle_pins.py (closed forms, hand-computed cases,
- * exact-sum error bound, order-sensitive cases).  The momentum / weight-decay
- * form is not given by the paper: it is pinned only by those closed forms and by
- * the special case momentum = wd = 0, which is eq. (1) with the averaged gradient.
+ * exact-sum error bound, order-sensitive cases); tests/test_oracle_mutants.py
+ * shows that copies of this file with one planted mistake each fail them.
+ * The momentum / weight-decay form is not given by the paper: it is pinned only
+ * by those closed forms and by the special case momentum = wd = 0, which is
+ * eq. (1) with the averaged gradient.
  */
 #include <stdint.h>
 #include <stddef.h>

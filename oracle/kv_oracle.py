@@ -35,7 +35,9 @@ _lib = None
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # KVO_LIBRARY names another build of kv_oracle.c to load instead: the mutation tests point it
+        # at copies with a planted mistake to show that the pins notice.
+        path = os.environ.get("KVO_LIBRARY") or _build.build(force=False)
         L = ctypes.CDLL(path)
         vpp = ctypes.POINTER(ctypes.c_void_p)
         fp = ctypes.POINTER(ctypes.c_float)
