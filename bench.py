@@ -65,6 +65,9 @@ def parse_args():
                          "instead of one allocation per key and rank")
     ap.add_argument("--rank-skew", type=int, default=0,
                     help="--flat-grads: rank r's buffer starts r * this many bytes into its allocation (multiple of 16)")
+    ap.add_argument("--graph", action="store_true",
+                    help="record one iteration per gradient set into a HIP graph (on a side stream, after eager "
+                         "warm-up steps) and time replays of the graphs instead of direct launches")
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--workgroups-per-cu", type=int, default=-1)
     ap.add_argument("--nontemporal", type=int, default=-1)
@@ -196,6 +199,13 @@ def main() -> int:
     if args.overlap:
         return overlap_mode(args)
 
+    side = None
+    if args.graph:
+        if args.schedule != "chained" or args.sets > 3:
+            print("--graph needs the chained schedule and at most 3 gradient sets", file=sys.stderr)
+            return 2
+        side = torch.cuda.Stream()          # the default stream cannot be captured
+        torch.cuda.set_stream(side)
     cfg = wl.get_config(args.config)
     if args.ranks or args.grad_dtype:
         import dataclasses
@@ -270,10 +280,23 @@ def main() -> int:
         def do_step(i):
             store.push_list(lists[i % nsets])
 
-    for i in range(args.warmup):
+    for i in range(max(args.warmup, nsets if args.graph else 0)):
         do_step(i)
     store.wait()
     torch.cuda.synchronize()
+    launches_per_replay = 0
+    if args.graph:
+        eager_step, graphs = do_step, []
+        for j in range(nsets):
+            before = store.launch_log(0)[0]
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                eager_step(j)
+            launches_per_replay = store.launch_log(0)[0] - before
+            graphs.append(g)
+
+        def do_step(i):
+            graphs[i % nsets].replay()
 
     store.timing_begin()
     t0 = time.perf_counter()
@@ -283,6 +306,8 @@ def main() -> int:
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ev_ms, launches = store.timing_end()
+    if args.graph:
+        launches = args.steps * launches_per_replay       # the store counts a captured launch once, at capture
 
     # per-step times from a second, separate pass: an event after every step costs about 2 us per
     # step, so it stays out of the timed region above
@@ -381,7 +406,7 @@ def main() -> int:
             "gradient_sets_cycled": nsets,
             "units": store.plan.num_units,
             "launches_per_step": launches_per_step,
-            "push_mode": args.push_mode,
+            "push_mode": args.push_mode + (", replayed from HIP graphs" if args.graph else ""),
             "schedule": args.schedule + (f" ({args.streams} streams, barrier every {args.outstanding} keys)"
                                          if args.schedule == "concurrent" else ""),
             "pull": "zero-copy (weights read in place in the arena)" if args.broadcast == "none" else

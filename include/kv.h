@@ -211,6 +211,21 @@ int kv_push(kv_store* store, int key, const void* const* dev_grads /* host [W] *
  * dev_grads is a host array [nkeys * W], key-major.  Either every key of the list
  * is accepted or none is. */
 int kv_push_list(kv_store* store, int nkeys, const int* keys /* host */, const void* const* dev_grads /* host */);
+/*
+ * Graph capture.  kv_push, kv_push_list and the pull functions may be called while the store's
+ * stream is being captured into a HIP graph (chained schedule only); every replay of the graph then
+ * repeats the launches with the gradient buffers and the optimizer parameters of the capture (the
+ * replica table of kv_set_broadcast is read as it is at replay time).
+ * Nothing can be uploaded during a capture, so the gradient buffers of every captured push must
+ * have been pushed once before it (their pointers then sit in a cached device table); a capture
+ * holds whole iterations.  A push that does not meet this returns KV_ERR_STATE and changes nothing.
+ * The table a captured launch reads is kept until kv_release_captures or kv_destroy; at most 3
+ * different sets of gradient buffers can be held this way (KV_ERR_STATE beyond).  Call
+ * kv_release_captures once the graphs are gone; replaying one afterwards is undefined.
+ * Every other call (kv_wait, kv_barrier, kv_set_*, timing) belongs outside the capture.  The launch
+ * log and the launch counter count a captured launch once, when it is recorded.
+ */
+int kv_release_captures(kv_store* store);
 
 /*
  * kv_pull: copies the key's current weights (numel fp32) to dev_out on the store's
@@ -232,9 +247,9 @@ int kv_pull_list(kv_store* store, int nkeys, const int* keys /* host */, void* c
 int kv_weights_ptr(kv_store* store, int key, void** dev_ptr_out);
 
 /*
- * kv_set_broadcast: the third phase of the paper's collective ("broadcast of the final result
- * across all the GPUs", which its pull performs by copying the aggregate back into every worker's
- * tensor), fused into the update: from the next launch on, the kernel that computes the key's new
+ * kv_set_broadcast: the third phase of the paper's collective (every GPU receives the final
+ * result; its pull does this by copying the aggregate back into every worker's tensor), fused
+ * into the update: from the next launch on, the kernel that computes the key's new
  * weights also writes them to n_replicas caller-owned device buffers of numel elements each, as
  * fp32 (dtype KV_F32) or rounded to nearest-even fp16 (KV_F16).  dev_dst: host array of n_replicas
  * device pointers, aligned to the element (all of them aligned to 16 bytes for fp32 replicas, 8 bytes

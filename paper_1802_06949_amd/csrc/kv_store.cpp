@@ -80,6 +80,10 @@ struct kv_store {
     int stage_next = 0;
 
     std::vector<std::vector<Deferred>> deferred;  // per unit
+    unsigned capture_mask = 0;                    // iteration being captured: tables that hold every key pushed so far
+    bool capture_iteration = false;               // the iteration in progress began inside a capture
+    bool capture_launch = false;                  // launches of the current push call are being captured
+    bool pinned[NSLOT] = {false, false, false, false};   // read by a captured launch: rows are never overwritten
 
     // fused broadcast of the updated weights to replica buffers
     int bcast_n = 0;
@@ -159,15 +163,25 @@ int check_key(kv_store* st, int key) {
 int table_for(kv_store* st, int s0, int s1, hipStream_t stream, const void* const** table_out) {
     const size_t W = (size_t)st->W;
     const size_t lo = (size_t)s0 * W, n = (size_t)(s1 - s0) * W;
-    for (int k = 0; k < NSLOT; ++k) {
-        const int slot = (st->last_slot + k) % NSLOT;
-        bool valid = true;
-        for (int sgm = s0; sgm < s1 && valid; ++sgm) valid = st->row_valid[slot][sgm] != 0;
-        if (valid && std::memcmp(&st->mirror[slot][lo], &st->cur_ptrs[lo], n * sizeof(void*)) == 0) {
-            st->last_slot = slot;
-            *table_out = st->d_slot[slot];
-            return KV_OK;
+    // A launch that is being captured may only read one of the tables its pushes were checked
+    // against, preferably one that an earlier capture already holds; the table is then held too.
+    for (int pass = st->capture_launch ? 0 : 1; pass < 2; ++pass) {
+        for (int k = 0; k < NSLOT; ++k) {
+            const int slot = (st->last_slot + k) % NSLOT;
+            if (st->capture_launch && (!(st->capture_mask >> slot & 1u) || (pass == 0 && !st->pinned[slot]))) continue;
+            bool valid = true;
+            for (int sgm = s0; sgm < s1 && valid; ++sgm) valid = st->row_valid[slot][sgm] != 0;
+            if (valid && std::memcmp(&st->mirror[slot][lo], &st->cur_ptrs[lo], n * sizeof(void*)) == 0) {
+                if (st->capture_launch) st->pinned[slot] = true;
+                st->last_slot = slot;
+                *table_out = st->d_slot[slot];
+                return KV_OK;
+            }
         }
+    }
+    if (st->capture_launch) {       // unreachable after capture_check; never upload into a capture
+        set_err(st->err, "captured launch found no cached pointer table");
+        return KV_ERR_STATE;
     }
     // Prefer the table used last if these rows are still free in it (keeps the rows of
     // one iteration together); else evict round robin.
@@ -175,8 +189,10 @@ int table_for(kv_store* st, int s0, int s1, hipStream_t stream, const void* cons
     bool free_rows = true;
     for (int sgm = s0; sgm < s1 && free_rows; ++sgm) free_rows = st->row_valid[slot][sgm] == 0;
     if (!free_rows) {
+        // a table that a captured launch reads is never a victim (at most NSLOT - 1 are pinned)
         slot = st->next_victim;
-        if (slot == st->last_slot) slot = (slot + 1) % NSLOT;
+        for (int tries = 0; tries < NSLOT && (st->pinned[slot] || slot == st->last_slot); ++tries) slot = (slot + 1) % NSLOT;
+        if (st->pinned[slot]) slot = st->last_slot;        // every other table is pinned; last_slot then is not
         st->next_victim = (slot + 1) % NSLOT;
     }
     const int chunk = st->stage_next;
@@ -369,6 +385,68 @@ void record_grads(kv_store* st, int key, const void* const* grads) {
     for (int r = 0; r < st->W; ++r) st->cur_ptrs[row + r] = grads[r];
 }
 
+// True while the store's stream records into a graph instead of executing.
+bool capturing(kv_store* st) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st->stream, &cs) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return cs == hipStreamCaptureStatusActive;
+}
+
+bool row_cached(const kv_store* st, int slot, int key, const void* const* grads) {
+    const int sgm = st->plan.key_seg[key];
+    if (!st->row_valid[slot][(size_t)sgm]) return false;
+    return std::memcmp(&st->mirror[slot][(size_t)sgm * (size_t)st->W], grads, (size_t)st->W * sizeof(void*)) == 0;
+}
+
+// While the stream is captured nothing can be uploaded (a recorded copy would read its pinned
+// staging chunk again at every replay, long after the chunk has been reused): the pointers of
+// every key pushed in the iteration must already sit, together, in a cached device table, i.e. the
+// same buffers were pushed before the capture.  capture_mask holds the tables that still qualify.
+// Checked before any state changes, so a refused push leaves the store as it was.
+int capture_check(kv_store* st, int nkeys, const int* keys, const void* const* grads) {
+    if (st->schedule != KV_SCHED_CHAINED) {
+        set_err(st->err, "only the chained schedule can be captured into a graph");
+        return KV_ERR_STATE;
+    }
+    const size_t W = (size_t)st->W;
+    const bool fresh = st->chain.pending_keys == 0 && st->chain.next_unit == 0;
+    if (!fresh && !st->capture_iteration) {
+        set_err(st->err, "push while the stream is being captured, but the iteration began before the capture: "
+                         "a capture holds whole iterations");
+        return KV_ERR_STATE;
+    }
+    unsigned mask = fresh ? (1u << NSLOT) - 1u : st->capture_mask;
+    int bad = -1;
+    for (int i = 0; i < nkeys && mask; ++i) {
+        unsigned m = 0;
+        for (int slot = 0; slot < NSLOT; ++slot)
+            if ((mask >> slot & 1u) && row_cached(st, slot, keys[i], grads + (size_t)i * W)) m |= 1u << slot;
+        if (!m) bad = keys[i];
+        mask = m;
+    }
+    if (!mask) {
+        set_err(st->err, "push of key %d while the stream is being captured: no cached pointer table holds its gradient "
+                         "buffers together with those of the keys pushed before it in this iteration (push the same "
+                         "buffers once before the capture)", bad);
+        return KV_ERR_STATE;
+    }
+    unsigned pinned_mask = 0;
+    int n_pinned = 0;
+    for (int slot = 0; slot < NSLOT; ++slot)
+        if (st->pinned[slot]) { pinned_mask |= 1u << slot; ++n_pinned; }
+    if (!(mask & pinned_mask) && n_pinned >= NSLOT - 1) {
+        set_err(st->err, "captured launches already hold %d sets of gradient buffers; kv_release_captures frees them",
+                NSLOT - 1);
+        return KV_ERR_STATE;
+    }
+    st->capture_mask = mask;
+    st->capture_iteration = true;
+    return KV_OK;
+}
+
 int pull_common(kv_store* st, int key, void* dst, int what) {
     if (!st) return KV_ERR_ARG;
     int rc = check_key(st, key);
@@ -382,7 +460,9 @@ int pull_common(kv_store* st, int key, void* dst, int what) {
         return KV_ERR_STATE;
     }
     if (st->chain.marked[key] && (st->flags & KV_FLAG_LAZY_LAUNCH)) {
+        st->capture_launch = st->capture_iteration && capturing(st);
         rc = drain_chain(st);                  // a pull is a reason to launch what is ready
+        st->capture_launch = false;
         if (rc != KV_OK) return rc;
     }
     if (st->chain.marked[key]) {               // pushed, unit not launched yet: run after that launch
@@ -671,6 +751,17 @@ int kv_push(kv_store* store, int key, const void* const* dev_grads) {
     if (rc != KV_OK) return rc;
     rc = check_grads(store, key, dev_grads);
     if (rc != KV_OK) return rc;
+    const bool captured = !store->in_list && capturing(store);
+    if (captured) {
+        if (store->chain.marked[key]) {
+            set_err(store->err, "key %d pushed twice before its unit ran", key);
+            return KV_ERR_STATE;
+        }
+        rc = capture_check(store, 1, &key, dev_grads);
+        if (rc != KV_OK) return rc;
+    } else if (!store->in_list && store->chain.pending_keys == 0 && store->chain.next_unit == 0) {
+        store->capture_iteration = false;
+    }
     if (store->schedule != KV_SCHED_CHAINED) {
         record_grads(store, key, dev_grads);
         return launch_key(store, key);
@@ -683,7 +774,10 @@ int kv_push(kv_store* store, int key, const void* const* dev_grads) {
     record_grads(store, key, dev_grads);
     // lazy stores let single pushes pile up until the whole iteration can go out as one launch
     if ((store->flags & KV_FLAG_LAZY_LAUNCH) && store->chain.pending_keys < store->plan.num_keys) return KV_OK;
-    return drain_chain(store);
+    store->capture_launch = captured;
+    rc = drain_chain(store);
+    store->capture_launch = false;
+    return rc;
 }
 
 int kv_push_list(kv_store* store, int nkeys, const int* keys, const void* const* dev_grads) {
@@ -692,6 +786,8 @@ int kv_push_list(kv_store* store, int nkeys, const int* keys, const void* const*
         set_err(store->err, "kv_push_list: bad arguments");
         return KV_ERR_ARG;
     }
+    const bool captured = capturing(store);
+    if (captured && store->schedule != KV_SCHED_CHAINED) return capture_check(store, 0, nullptr, nullptr);
     if (store->schedule != KV_SCHED_CHAINED) {
         // keys go out one by one, in list order
         store->in_list = true;
@@ -712,6 +808,12 @@ int kv_push_list(kv_store* store, int nkeys, const int* keys, const void* const*
             return KV_ERR_STATE;
         }
     }
+    if (captured) {
+        int rc = capture_check(store, nkeys, keys, dev_grads);
+        if (rc != KV_OK) return rc;
+    } else if (store->chain.pending_keys == 0 && store->chain.next_unit == 0) {
+        store->capture_iteration = false;
+    }
     for (int i = 0; i < nkeys; ++i) {
         if (store->chain.mark(keys[i]) != KV_OK) {          // duplicate inside the list: undo
             for (int j = 0; j < i; ++j) {
@@ -724,7 +826,10 @@ int kv_push_list(kv_store* store, int nkeys, const int* keys, const void* const*
         }
     }
     for (int i = 0; i < nkeys; ++i) record_grads(store, keys[i], dev_grads + (size_t)i * store->W);
-    return drain_chain(store);
+    store->capture_launch = captured;
+    const int rc = drain_chain(store);
+    store->capture_launch = false;
+    return rc;
 }
 
 int kv_pull(kv_store* store, int key, void* dev_out_f32) { return pull_common(store, key, dev_out_f32, 0); }
@@ -882,6 +987,13 @@ int kv_set_broadcast(kv_store* store, int key, int n_replicas, void* const* dev_
         store->h_bcast[row + r] = (n_replicas > 0 && store->plan.numel[key] > 0) ? dev_dst[r] : nullptr;
     KV_HIP(store, hipMemcpy(store->d_bcast + row, &store->h_bcast[row], (size_t)store->bcast_n * sizeof(void*),
                             hipMemcpyHostToDevice));
+    return KV_OK;
+}
+
+int kv_release_captures(kv_store* store) {
+    if (!store) return KV_ERR_ARG;
+    for (int i = 0; i < NSLOT; ++i) store->pinned[i] = false;
+    store->capture_mask = 0;
     return KV_OK;
 }
 

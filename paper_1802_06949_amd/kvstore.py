@@ -92,6 +92,7 @@ def load_library() -> ctypes.CDLL:
     sig("kv_set_broadcast", c_int, c_vp, c_int, c_int, P(c_vp), c_int)
     sig("kv_set_schedule", c_int, c_vp, c_int, c_int, c_int)
     sig("kv_barrier", c_int, c_vp)
+    sig("kv_release_captures", c_int, c_vp)
     sig("kv_store_plan", c_vp, c_vp)
     sig("kv_launch_log", c_int, c_vp, P(c_i64), P(c_int), P(c_int), c_int)
     sig("kv_timing_begin", c_int, c_vp)
@@ -315,6 +316,10 @@ class KVStore:
 
     def push_list(self, pl: PushList) -> None:
         self._check(self._L.kv_push_list(self._h, pl.n, pl.keys, pl.ptrs))
+
+    def release_captures(self) -> None:
+        """Lets the pointer tables that captured launches read be reused (call once the graphs are gone)."""
+        self._check(self._L.kv_release_captures(self._h))
 
     # --- pull
     def pull(self, key: int, out) -> None:
