@@ -201,8 +201,8 @@ def main() -> int:
 
     side = None
     if args.graph:
-        if args.schedule != "chained" or args.sets > 3:
-            print("--graph needs the chained schedule and at most 3 gradient sets", file=sys.stderr)
+        if args.schedule != "chained" or args.sets > 7:
+            print("--graph needs the chained schedule and at most 7 gradient sets", file=sys.stderr)
             return 2
         side = torch.cuda.Stream()          # the default stream cannot be captured
         torch.cuda.set_stream(side)

@@ -219,7 +219,7 @@ int kv_push_list(kv_store* store, int nkeys, const int* keys /* host */, const v
  * Nothing can be uploaded during a capture, so the gradient buffers of every captured push must
  * have been pushed once before it (their pointers then sit in a cached device table); a capture
  * holds whole iterations.  A push that does not meet this returns KV_ERR_STATE and changes nothing.
- * The table a captured launch reads is kept until kv_release_captures or kv_destroy; at most 3
+ * The table a captured launch reads is kept until kv_release_captures or kv_destroy; at most 7
  * different sets of gradient buffers can be held this way (KV_ERR_STATE beyond).  Call
  * kv_release_captures once the graphs are gone; replaying one afterwards is undefined.
  * Every other call (kv_wait, kv_barrier, kv_set_*, timing) belongs outside the capture.  The launch

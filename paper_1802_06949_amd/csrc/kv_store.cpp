@@ -35,7 +35,7 @@ void set_err(std::string& dst, const char* fmt, ...) {
     dst = buf;
 }
 
-constexpr int NSLOT = 4;    // cached device pointer tables
+constexpr int NSLOT = 8;    // cached device pointer tables
 constexpr int NSTAGE = 8;   // pinned staging chunks in flight
 constexpr int LOG_CAP = 4096;
 
@@ -68,7 +68,7 @@ struct kv_store {
 
     size_t table_elems = 0;                       // num_segs * W
     std::vector<const void*> cur_ptrs;            // host: pointers of the pushes not yet launched
-    const void** d_slot[NSLOT] = {nullptr, nullptr, nullptr, nullptr};
+    const void** d_slot[NSLOT] = {};
     std::vector<const void*> mirror[NSLOT];       // host copy of what each device table holds
     std::vector<uint8_t> row_valid[NSLOT];        // per segment
     int last_slot = 0;
@@ -83,7 +83,7 @@ struct kv_store {
     unsigned capture_mask = 0;                    // iteration being captured: tables that hold every key pushed so far
     bool capture_iteration = false;               // the iteration in progress began inside a capture
     bool capture_launch = false;                  // launches of the current push call are being captured
-    bool pinned[NSLOT] = {false, false, false, false};   // read by a captured launch: rows are never overwritten
+    bool pinned[NSLOT] = {};                      // read by a captured launch: rows are never overwritten
 
     // fused broadcast of the updated weights to replica buffers
     int bcast_n = 0;

@@ -152,7 +152,7 @@ def test_only_the_chained_schedule_can_be_captured():
             pair.close()
 
 
-def test_at_most_three_buffer_sets_are_held_for_graphs():
+def test_at_most_seven_buffer_sets_are_held_for_graphs():
     import torch
     import paper_1802_06949_amd as kv
     s = torch.cuda.Stream()
@@ -160,12 +160,12 @@ def test_at_most_three_buffer_sets_are_held_for_graphs():
         pair = _pair(s)
         try:
             K = len(NUMEL)
-            sets = [_grads(20 + i) for i in range(4)]
+            sets = [_grads(20 + i) for i in range(8)]
             dev = [pair.upload(g) for g in sets]
             lists = [pair.gpu.make_push_list(list(range(K)), d) for d in dev]
             marker = torch.zeros(8, device="cuda")
             graphs, codes = [], []
-            for i in range(4):
+            for i in range(8):
                 pair.step(sets[i], dev=dev[i])                         # eager: caches this set's table
                 g = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(g, stream=s):
@@ -175,24 +175,24 @@ def test_at_most_three_buffer_sets_are_held_for_graphs():
                     except kv.KVError as e:
                         codes.append((i, e.status))
                 graphs.append(g)
-            assert codes == [(3, KV_ERR_STATE)]                     # three tables are held, the fourth is refused
+            assert codes == [(7, KV_ERR_STATE)]                     # seven tables are held, the eighth is refused
             pair.compare("after the captures")
             # eager steps with ever new buffers have one table left to go through; the held ones stay intact
             for i in range(3):
                 pair.step(_grads(30 + i))
-            for i in (2, 0, 1):
+            for i in (6, 2, 0, 5, 1, 3, 4):
                 graphs[i].replay()
                 pair.cpu.step(sets[i])
                 pair.gpu.wait()
                 pair.compare(f"replay of graph {i}")
             pair.gpu.release_captures()
-            pair.step(sets[3], dev=dev[3])
+            pair.step(sets[7], dev=dev[7])
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=s):
-                pair.gpu.push_list(lists[3])
+                pair.gpu.push_list(lists[7])
             g.replay()
-            pair.cpu.step(sets[3])
+            pair.cpu.step(sets[7])
             pair.gpu.wait()
-            pair.compare("replay of the fourth set after the release")
+            pair.compare("replay of the eighth set after the release")
         finally:
             pair.close()
