@@ -172,7 +172,7 @@ template <int NV> struct FoldSel<NV, true> { using type = FoldPair<NV>; };
 #define KV_CONST __attribute__((address_space(4)))
 #define KV_GLOBAL __attribute__((address_space(1)))
 
-// Sum over ranks of the 16-byte vector that starts `boff` bytes into every rank's copy of the key.
+// Sum over ranks of the gradient vector (4 values) that starts `boff` bytes into every rank's copy of the key.
 template <bool F16, int WT, bool PAIRWISE, bool NT>
 __device__ __forceinline__ void reduce_vec(const uint64_t KV_CONST* gp, int W, int64_t boff,
                                            float (&s)[Grad<F16>::VEC]) {
@@ -243,9 +243,9 @@ __device__ __forceinline__ void sgd_update(float s, float w, float m, float resc
     w_new = w + dw;
 }
 
-// Third phase of the paper's collective ("broadcast of the final result across all the GPUs"):
-// the updated weights also go to `n` replica buffers of the key, as fp32 or rounded to nearest-even
-// fp16, in the same pass.  row == nullptr or a null first pointer: the key has no replicas.
+// Third phase of the paper's collective (every GPU receives the final result): the updated
+// weights also go to `n` replica buffers of the key, as fp32 or rounded to nearest-even fp16, in
+// the same pass.  row == nullptr or a null first pointer: the key has no replicas.
 struct Bcast {
     const uint64_t KV_CONST* row;
     int n;
