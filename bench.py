@@ -376,6 +376,17 @@ def main() -> int:
             ceil[f"read_{label}_GBps"] = rate(lambda: kv.read_bytes(a, nb), nb)
             ceil[f"copy_{label}_GBps"] = rate(lambda: kv.copy_bytes(b, a, nb), 2 * nb)
             del a, b
+        # mixes of read and written streams of 512 MiB each with the fused kernel's access pattern (nothing
+        # fits the memory-side cache), buffers as allocated and staggered by 4 KB per buffer
+        per = 512 << 20
+        pool = [torch.zeros(per + 64 * 4096, dtype=torch.uint8, device="cuda") for _ in range(18)]
+        for label, stagger in (("aligned", 0), ("staggered_4KB", 4096)):
+            bufs = [b[i * stagger:i * stagger + per] for i, b in enumerate(pool)]
+            for n_read, n_write in ((1, 0), (16, 0), (1, 1), (2, 2), (8, 8), (16, 1), (16, 2)):
+                rd, wr = bufs[:n_read], bufs[n_read:n_read + n_write]
+                ceil[f"mix_{n_read}r_{n_write}w_{label}_GBps"] = rate(lambda: kv.stream_mix(rd, wr, per),
+                                                                     (n_read + n_write) * per, reps=10)
+        del pool
         extra["ceilings"] = ceil
 
     if args.calib_copy > 0:

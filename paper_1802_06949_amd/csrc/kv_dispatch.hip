@@ -34,6 +34,27 @@ __global__ void __launch_bounds__(KV_THREADS) kv_read_kernel(const f32x4* __rest
     if (acc.x == -12345.678f && acc.y == 3.25f) sink[0] = acc;
 }
 
+// R read streams and n_write written streams with the access pattern of the fused kernel: one
+// workgroup per 4 KB tile of every stream, every load in flight before the first store.
+struct KvMixArgs {
+    const f32x4* rd[32];
+    f32x4* wr[8];
+};
+template <int R>
+__global__ void __launch_bounds__(KV_THREADS) kv_mix_kernel(const KvMixArgs a, int n_write, size_t nvec) {
+    const size_t i = (size_t)blockIdx.x * KV_THREADS + threadIdx.x;
+    if (i >= nvec) return;
+    f32x4 v[R];
+#pragma unroll
+    for (int s = 0; s < R; ++s) v[s] = __builtin_nontemporal_load(a.rd[s] + i);
+    f32x4 acc = v[0];
+#pragma unroll
+    for (int s = 1; s < R; ++s) acc += v[s];
+    for (int s = 0; s < n_write; ++s) a.wr[s][i] = acc;
+    // with no written stream the sum goes nowhere; it can never equal the sentinel, but the compiler cannot know
+    if (n_write == 0 && acc.x == -12345.678f && acc.y == 3.25f) const_cast<f32x4*>(a.rd[0])[i] = acc;
+}
+
 // Stand-in for a compute-bound backward operator: every lane first runs `spin` dependent
 // multiply-adds (no memory traffic), then copies its share.  The spun value can never equal
 // the sentinel, but the compiler cannot know that, so the loop stays.
@@ -104,5 +125,23 @@ hipError_t kv_launch_copy(void* dst, const void* src, size_t bytes, hipStream_t 
     if (blocks > (1u << 22)) blocks = 1u << 22;
     hipLaunchKernelGGL(kv_copy_kernel, dim3((unsigned)blocks), dim3(KV_THREADS), 0, stream,
                        static_cast<f32x4*>(dst), static_cast<const f32x4*>(src), nvec);
+    return hipGetLastError();
+}
+
+hipError_t kv_launch_mix(void* const* bufs, int n_read, int n_write, size_t bytes, hipStream_t stream) {
+    const size_t nvec = bytes / 16;
+    if (nvec == 0) return hipSuccess;
+    const size_t blocks = (nvec + KV_THREADS - 1) / KV_THREADS;
+    if (n_read > 32 || n_write > 8 || blocks > 0x7FFFFFFFu) return hipErrorInvalidValue;
+    KvMixArgs a{};
+    for (int s = 0; s < n_read; ++s) a.rd[s] = static_cast<const f32x4*>(bufs[s]);
+    for (int s = 0; s < n_write; ++s) a.wr[s] = static_cast<f32x4*>(bufs[n_read + s]);
+#define KV_MIX(R) \
+    case R: hipLaunchKernelGGL(kv_mix_kernel<R>, dim3((unsigned)blocks), dim3(KV_THREADS), 0, stream, a, n_write, nvec); break;
+    switch (n_read) {
+        KV_MIX(1) KV_MIX(2) KV_MIX(4) KV_MIX(8) KV_MIX(16) KV_MIX(32)
+        default: return hipErrorInvalidValue;
+    }
+#undef KV_MIX
     return hipGetLastError();
 }

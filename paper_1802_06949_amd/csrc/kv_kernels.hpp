@@ -30,3 +30,9 @@ hipError_t kv_launch_gather(const KvTile* tiles, int64_t tile_lo, int64_t tile_h
 
 // Reads `bytes` bytes (multiple of 16) and writes nothing: a measured ceiling for reads.
 hipError_t kv_launch_read(const void* src, size_t bytes, hipStream_t stream);
+
+// One pass over n_read (1, 2, 4, 8, 16 or 32) read buffers and n_write (0..8) written buffers of
+// `bytes` bytes each (multiple of 16), read buffers first in `bufs` (host array of device pointers):
+// every lane sums its 16-byte vector of the read buffers and stores the sum to every written buffer.
+// A measured ceiling for a mix of streams.
+hipError_t kv_launch_mix(void* const* bufs, int n_read, int n_write, size_t bytes, hipStream_t stream);

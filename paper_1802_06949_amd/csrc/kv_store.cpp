@@ -1159,6 +1159,26 @@ int kv_read_bytes(const void* dev_src, size_t bytes, void* hip_stream) {
     return KV_OK;
 }
 
+int kv_stream_mix(void* const* dev_bufs, int n_read, int n_write, size_t bytes, void* hip_stream) {
+    const bool r_ok = n_read == 1 || n_read == 2 || n_read == 4 || n_read == 8 || n_read == 16 || n_read == 32;
+    if (!dev_bufs || !r_ok || n_write < 0 || n_write > 8 || (bytes & 15u)) {
+        set_err(g_err, "kv_stream_mix: n_read must be 1, 2, 4, 8, 16 or 32, n_write 0..8, bytes a multiple of 16");
+        return KV_ERR_ARG;
+    }
+    for (int s = 0; s < n_read + n_write; ++s) {
+        if (!dev_bufs[s] || ((uintptr_t)dev_bufs[s] & 15u)) {
+            set_err(g_err, "kv_stream_mix: buffer %d is null or not aligned to 16 bytes", s);
+            return KV_ERR_ARG;
+        }
+    }
+    hipError_t e = kv_launch_mix(dev_bufs, n_read, n_write, bytes, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) {
+        set_err(g_err, "kv_stream_mix: %s", hipGetErrorString(e));
+        return KV_ERR_HIP;
+    }
+    return KV_OK;
+}
+
 const char* kv_last_error(const kv_store* store) { return store ? store->err.c_str() : g_err.c_str(); }
 
 }  // extern "C"

@@ -101,6 +101,7 @@ def load_library() -> ctypes.CDLL:
     sig("kv_timing_intervals", c_int, c_vp, P(ctypes.c_float), c_int)
     sig("kv_copy_bytes", c_int, c_vp, c_vp, c_sz, c_vp)
     sig("kv_read_bytes", c_int, c_vp, c_sz, c_vp)
+    sig("kv_stream_mix", c_int, P(c_vp), c_int, c_int, c_sz, c_vp)
     sig("kv_last_error", ctypes.c_char_p, c_vp)
     _lib = L
     return L
@@ -413,5 +414,19 @@ def read_bytes(src, nbytes: int, stream: Optional[int] = None) -> None:
         import torch
         stream = torch.cuda.current_stream().cuda_stream
     rc = L.kv_read_bytes(ctypes.c_void_p(src.data_ptr()), int(nbytes), ctypes.c_void_p(int(stream)))
+    if rc != 0:
+        raise KVError(rc, _global_error(L))
+
+
+def stream_mix(read_bufs: Sequence, write_bufs: Sequence, nbytes: int, stream: Optional[int] = None) -> None:
+    """kv_stream_mix: sums 16-byte vectors of the read buffers into every written buffer (a measured ceiling for a
+    mix of read and write streams)."""
+    L = load_library()
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    bufs = list(read_bufs) + list(write_bufs)
+    arr = (ctypes.c_void_p * max(len(bufs), 1))(*[int(b.data_ptr()) for b in bufs])
+    rc = L.kv_stream_mix(arr, len(read_bufs), len(write_bufs), int(nbytes), ctypes.c_void_p(int(stream)))
     if rc != 0:
         raise KVError(rc, _global_error(L))

@@ -53,3 +53,31 @@ def test_engine_driven_steps_match_the_oracle(threads, cfg_id, descending):
             loop.close()
         eng.close()
         pair.close()
+
+
+def test_stream_mix_diagnostic_sums_its_read_buffers():
+    """kv_stream_mix (the measured ceiling for mixes of streams): every written buffer receives the sum, in buffer
+    order, of the read buffers; bad shapes are refused."""
+    import torch
+    import paper_1802_06949_amd as kv
+    n = 3 * 1024 + 8                                     # floats: several 4 KB tiles and a ragged one
+    rng = np.random.Generator(np.random.SFC64([77, 1]))
+    for n_read, n_write in ((1, 1), (2, 3), (4, 0), (8, 2), (16, 1), (32, 8)):
+        host = [rng.standard_normal(n).astype(np.float32) for _ in range(n_read)]
+        rd = [torch.from_numpy(h).cuda() for h in host]
+        wr = [torch.full((n,), 7.0, device="cuda") for _ in range(n_write)]
+        kv.stream_mix(rd, wr, n * 4)
+        torch.cuda.synchronize()
+        want = host[0].copy()
+        for h in host[1:]:
+            want = want + h                              # float32, left to right, as the kernel adds
+        for w in wr:
+            assert np.array_equal(w.cpu().numpy().view(np.uint32), want.view(np.uint32))
+        for h, d in zip(host, rd):
+            assert np.array_equal(d.cpu().numpy(), h)    # read buffers untouched
+    a = torch.zeros(64, device="cuda")
+    for bad in (([a] * 3, [a]), ([a], [a] * 9), ([], [a])):
+        with pytest.raises(kv.KVError):
+            kv.stream_mix(bad[0], bad[1], 256)
+    with pytest.raises(kv.KVError):
+        kv.stream_mix([a], [a], 250)                     # not a multiple of 16
