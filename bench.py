@@ -69,6 +69,7 @@ def parse_args():
                     help="record one iteration per gradient set into a HIP graph (on a side stream, after eager "
                          "warm-up steps) and time replays of the graphs instead of direct launches")
     ap.add_argument("--unroll", type=int, default=0)
+    ap.add_argument("--lane-elems", type=int, default=0)
     ap.add_argument("--workgroups-per-cu", type=int, default=-1)
     ap.add_argument("--nontemporal", type=int, default=-1)
     ap.add_argument("--xcd-remap", type=int, default=-1)
@@ -248,7 +249,7 @@ def main() -> int:
 
     store = kv.KVStore(cfg.numel, cfg.W, cfg.grad_dtype, cfg.bucket_bytes, lr=cfg.lr, momentum=cfg.momentum, wd=cfg.wd,
                        keep_sum=False, lazy=args.lazy, unroll=args.unroll, workgroups_per_cu=args.workgroups_per_cu,
-                       nontemporal=args.nontemporal, xcd_remap=args.xcd_remap)
+                       nontemporal=args.nontemporal, xcd_remap=args.xcd_remap, lane_elems=args.lane_elems)
     for k, w in enumerate(weights):
         if w.size:
             store.set_weights(k, torch.from_numpy(w).cuda())

@@ -109,7 +109,10 @@ typedef struct kv_sgd_params {
 
 /*
  * Launch tuning; pass NULL for defaults.  None of these changes any result bit.
- *   unroll            4-element vectors per thread per rank in one tile: 1, 2 or 4 (0 = default)
+ *   unroll            vectors per thread per rank in one tile: 1, 2 or 4 (0 = default)
+ *   lane_elems        consecutive elements per vector, i.e. per thread and load instruction: 1, 2 or 4
+ *                     (0 = default); a tile is 256 * lane_elems * unroll elements; (lane_elems, unroll)
+ *                     must be one of (4,1) (4,2) (4,4) (2,1) (2,2) (1,1) (1,2) (1,4)
  *   workgroups_per_cu cap of resident workgroups per compute unit for the grid-stride
  *                     loop over tiles; 0 = one workgroup per tile
  *   nontemporal       cache policy: bit 0 = gradient loads carry the non-temporal hint; plus the policy
@@ -124,6 +127,7 @@ typedef struct kv_tuning {
     int workgroups_per_cu;
     int nontemporal;
     int xcd_remap;
+    int lane_elems;
 } kv_tuning;
 
 /* ------------------------------------------------------------------ plan (host only)

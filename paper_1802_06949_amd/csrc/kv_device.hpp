@@ -27,7 +27,9 @@ struct KvLaunchArgs {
     int64_t tile_lo;              // first tile of this launch
     int64_t tile_hi;              // one past the last tile
     int32_t W;
-    int32_t xcd_remap;
+    int32_t xcd_remap;            // G: consecutive tiles per XCD block (0 = tiles dealt one by one)
+    int32_t xcd_shift;            // log2(G) if G is a power of two, else -1
+    uint32_t xcd_span;            // tiles of the launch rounded up to whole rows of 8 G (the launch's tiles if G = 0)
     float lr, momentum, wd, rescale;
 };
 
@@ -37,10 +39,11 @@ struct KvKernelSel {
     int W;
     int pairwise;      // 0: rank-order left fold, 1: balanced tree
     int keep_sum;
-    int unroll;        // 1, 2, 4
+    int unroll;        // vectors per lane and rank: 1, 2, 4
+    int lane_elems;    // consecutive elements per vector: 1, 2, 4
     int nontemporal;
 };
 
-// Elements per tile: every lane owns 4 consecutive elements per unrolled vector, whatever the
-// gradient dtype.
-constexpr int kv_tile_elems(int /*grad_f16*/, int unroll) { return KV_THREADS * 4 * unroll; }
+// Elements per tile: every lane owns `unroll` vectors of `lane_elems` consecutive elements,
+// whatever the gradient dtype.
+constexpr int kv_tile_elems(int lane_elems, int unroll) { return KV_THREADS * lane_elems * unroll; }

@@ -7,9 +7,9 @@
 // The path is a pure streaming pass: per parameter element it reads W gradient
 // values once, reads w and m, and writes w' and m'.  There is no reuse, so there
 // is no LDS staging and no MFMA; what matters is that every lane issues
-// independent vector loads (128 bits of fp32 or 64 bits of fp16 gradients per rank; all W
-// ranks, and `U` vectors per rank, are in flight before the first add) and that a
-// wavefront's 64 lanes cover contiguous memory per load instruction.
+// independent loads (N = 1, 2 or 4 consecutive elements per lane and rank; all W ranks, and `U`
+// such vectors per rank, are in flight before the first add) and that a wavefront's 64 lanes cover
+// contiguous memory per load instruction.
 //
 // Arithmetic contract (must match bit for bit what the header of the C ABI
 // states): each element is owned by one lane for all W ranks, the ranks are
@@ -30,33 +30,65 @@
 
 namespace {
 
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
-template <bool F16> struct Grad;
-template <> struct Grad<false> {
-    using elem = float;
-    using vec = f32x4;
-    static constexpr int VEC = 4;
-    static __device__ __forceinline__ void widen(const vec& v, float (&o)[4]) {
-        o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
-    }
-    static __device__ __forceinline__ float widen1(elem e) { return e; }
-};
-// Half-precision gradients are read 8 bytes (4 values) per lane, not 16: a lane then owns 4
-// consecutive elements, exactly one 16-byte vector of w and of m, so that every load and store of
-// the fp32 state covers whole cache lines.  (With 8 halves per lane the state accesses of a
-// wavefront touch every line half, twice; measured 9 % slower on ResNet-50 W=32.)
-template <> struct Grad<true> {
-    using elem = _Float16;
-    using vec = f16x4;
-    static constexpr int VEC = 4;
-    static __device__ __forceinline__ void widen(const vec& v, float (&o)[4]) {
+// N consecutive fp32 / fp16 values as one register-resident vector (a plain scalar for N = 1).
+template <int N> struct FVec;
+template <> struct FVec<1> { using type = float; };
+template <> struct FVec<2> { using type = f32x2; };
+template <> struct FVec<4> { using type = f32x4; };
+template <int N> struct HVec;
+template <> struct HVec<1> { using type = _Float16; };
+template <> struct HVec<2> { using type = f16x2; };
+template <> struct HVec<4> { using type = f16x4; };
+
+template <int N, typename V>
+__device__ __forceinline__ float lane_get(const V& v, int i) {
+    if constexpr (N == 1) return (float)v;
+    else return (float)v[i];
+}
+template <int N>
+__device__ __forceinline__ typename FVec<N>::type pack_f32(const float (&a)[N]) {
+    if constexpr (N == 1) return a[0];
+    else {
+        typename FVec<N>::type v;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) o[i] = (float)v[i];      // exact: every binary16 value is a binary32 value
+        for (int i = 0; i < N; ++i) v[i] = a[i];
+        return v;
     }
-    static __device__ __forceinline__ float widen1(elem e) { return (float)e; }
+}
+template <int N>
+__device__ __forceinline__ typename HVec<N>::type pack_f16(const float (&a)[N]) {       // round to nearest even
+    if constexpr (N == 1) return (_Float16)a[0];
+    else {
+        typename HVec<N>::type v;
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] = (_Float16)a[i];
+        return v;
+    }
+}
+
+// Gradient vector of one lane: N consecutive elements.  Whatever the gradient dtype, a lane then
+// owns exactly one N-element vector of w and of m, so that every load and store of the fp32 state
+// of a wavefront covers whole cache lines.  (With 8 halves per lane and two state vectors the
+// state accesses touched every line half, twice; measured 9 % slower on ResNet-50 W=32.)
+template <bool F16, int N> struct Grad {
+    using elem = float;
+    using vec = typename FVec<N>::type;
 };
+template <int N> struct Grad<true, N> {
+    using elem = _Float16;
+    using vec = typename HVec<N>::type;
+};
+// Widening is exact: every binary16 value is a binary32 value.
+template <int N, typename V>
+__device__ __forceinline__ void widen(const V& v, float (&o)[N]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) o[i] = lane_get<N>(v, i);
+}
 
 // Cache-policy mask of a kernel instantiation:
 //   bit 0       gradient loads carry the non-temporal hint
@@ -68,27 +100,32 @@ __device__ __forceinline__ T load_grad(const T* p) {
     if constexpr (NT) return __builtin_nontemporal_load(p);
     else return *p;
 }
-template <bool NT>
-__device__ __forceinline__ f32x4 load_state(const float* p) {
-    if constexpr (NT) return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
-    else return *reinterpret_cast<const f32x4*>(p);
+template <bool NT, int N>
+__device__ __forceinline__ typename FVec<N>::type load_state(const float* p) {
+    using V = typename FVec<N>::type;
+    if constexpr (NT) return __builtin_nontemporal_load(reinterpret_cast<const V*>(p));
+    else return *reinterpret_cast<const V*>(p);
 }
-// Stores 16 bytes at element `k` of the uniform base pointer `base`.  Policy 8 uses a raw
+// Stores N floats at element `k` of the uniform base pointer `base`.  Policies 8 and 12 use a raw
 // buffer store, whose cache-policy operand can carry the sc1 bit (write through L2 to memory
 // at once instead of leaving a dirty line in L2); the buffer descriptor spans exactly the
 // bytes handed in, so an out-of-range lane could not write.  0x00020000 is word 3 of a raw
 // (untyped, 32-bit data format) buffer descriptor on gfx9-family targets.
-template <int POL>
-__device__ __forceinline__ void store_state(float* base, int k, unsigned span_bytes, const f32x4& v) {
+template <int POL, int N>
+__device__ __forceinline__ void store_state(float* base, int k, unsigned span_bytes, const typename FVec<N>::type& v) {
+    using V = typename FVec<N>::type;
     if constexpr (POL == 4) {
-        __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(base + k));
+        __builtin_nontemporal_store(v, reinterpret_cast<V*>(base + k));
     } else if constexpr (POL == 8 || POL == 12) {
+        typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
         typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(base, 0, span_bytes, 0x00020000);
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rsrc, k * 4, 0,
-                                               POL == 12 ? /*sc1 + nt*/ 18 : /*sc1*/ 16);
+        constexpr int aux = POL == 12 ? /*sc1 + nt*/ 18 : /*sc1*/ 16;
+        if constexpr (N == 4) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rsrc, k * 4, 0, aux);
+        else if constexpr (N == 2) __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, v), rsrc, k * 4, 0, aux);
+        else __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), rsrc, k * 4, 0, aux);
     } else {
-        *reinterpret_cast<f32x4*>(base + k) = v;
+        *reinterpret_cast<V*>(base + k) = v;
     }
 }
 
@@ -172,14 +209,11 @@ template <int NV> struct FoldSel<NV, true> { using type = FoldPair<NV>; };
 #define KV_CONST __attribute__((address_space(4)))
 #define KV_GLOBAL __attribute__((address_space(1)))
 
-// Sum over ranks of the gradient vector (4 values) that starts `boff` bytes into every rank's copy of the key.
-template <bool F16, int WT, bool PAIRWISE, bool NT>
-__device__ __forceinline__ void reduce_vec(const uint64_t KV_CONST* gp, int W, int64_t boff,
-                                           float (&s)[Grad<F16>::VEC]) {
-    using G = Grad<F16>;
-    using V = typename G::vec;
-    constexpr int NV = G::VEC;
-    typename FoldSel<NV, PAIRWISE>::type f;
+// Sum over ranks of the gradient vector (N values) that starts `boff` bytes into every rank's copy of the key.
+template <bool F16, int N, int WT, bool PAIRWISE, bool NT>
+__device__ __forceinline__ void reduce_vec(const uint64_t KV_CONST* gp, int W, int64_t boff, float (&s)[N]) {
+    using V = typename Grad<F16, N>::vec;
+    typename FoldSel<N, PAIRWISE>::type f;
     if constexpr (WT > 0) {
         constexpr int CH = WT > 16 ? 16 : WT;      // ranks whose loads are issued back to back
 #pragma unroll
@@ -189,8 +223,8 @@ __device__ __forceinline__ void reduce_vec(const uint64_t KV_CONST* gp, int W, i
             for (int j = 0; j < CH; ++j) g[j] = load_grad<NT>((const V KV_GLOBAL*)(gp[r0 + j] + (uint64_t)boff));
 #pragma unroll
             for (int j = 0; j < CH; ++j) {
-                float t[NV];
-                G::widen(g[j], t);
+                float t[N];
+                widen<N>(g[j], t);
                 f.push(t);
             }
         }
@@ -203,8 +237,8 @@ __device__ __forceinline__ void reduce_vec(const uint64_t KV_CONST* gp, int W, i
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 if (r0 + j < W) {
-                    float t[NV];
-                    G::widen(g[j], t);
+                    float t[N];
+                    widen<N>(g[j], t);
                     f.push(t);
                 }
             }
@@ -217,12 +251,11 @@ __device__ __forceinline__ void reduce_vec(const uint64_t KV_CONST* gp, int W, i
 // that are not 16-byte aligned).
 template <bool F16, int WT, bool PAIRWISE>
 __device__ __forceinline__ float reduce_one(const uint64_t KV_CONST* gp, int W, int64_t e) {
-    using G = Grad<F16>;
-    using E = typename G::elem;
+    using E = typename Grad<F16, 1>::elem;
     typename FoldSel<1, PAIRWISE>::type f;
     const int n = WT > 0 ? WT : W;
     for (int r = 0; r < n; ++r) {
-        float t[1] = {G::widen1(((const E KV_GLOBAL*)gp[r])[e])};
+        float t[1] = {(float)((const E KV_GLOBAL*)gp[r])[e]};
         f.push(t);
     }
     float o[1];
@@ -252,15 +285,15 @@ struct Bcast {
     int f16;
 };
 
-__device__ __forceinline__ void bcast4(const Bcast& b, int64_t e, const f32x4& wn) {
+template <int N>
+__device__ __forceinline__ void bcast_vec(const Bcast& b, int64_t e, const float (&wn)[N]) {
     if (b.n == 0) return;
     if (b.f16) {
-        f16x4 h;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) h[c] = (_Float16)wn[c];
-        for (int r = 0; r < b.n; ++r) *(f16x4 KV_GLOBAL*)(b.row[r] + (uint64_t)e * 2u) = h;
+        const typename HVec<N>::type h = pack_f16<N>(wn);
+        for (int r = 0; r < b.n; ++r) *(typename HVec<N>::type KV_GLOBAL*)(b.row[r] + (uint64_t)e * 2u) = h;
     } else {
-        for (int r = 0; r < b.n; ++r) *(f32x4 KV_GLOBAL*)(b.row[r] + (uint64_t)e * 4u) = wn;
+        const typename FVec<N>::type v = pack_f32<N>(wn);
+        for (int r = 0; r < b.n; ++r) *(typename FVec<N>::type KV_GLOBAL*)(b.row[r] + (uint64_t)e * 4u) = v;
     }
 }
 
@@ -287,31 +320,26 @@ __device__ __forceinline__ void scalar_element(const uint64_t KV_CONST* gp, int 
     bcast1(bc, e, wn);
 }
 
-// Updates the four elements k..k+3 of the tile whose arenas start at wp / mp / sp.
-template <bool KEEP, int NTS>
-__device__ __forceinline__ void update_store4(const float* s4, const f32x4& wv, const f32x4& mv, float* wp, float* mp,
-                                              float* sp, int k, unsigned span_bytes, const Bcast& bc, int64_t e,
-                                              const KvLaunchArgs& a) {
-    f32x4 wn, mn, sv;
+// Updates the N elements k..k+N-1 of the tile whose arenas start at wp / mp / sp.
+template <bool KEEP, int NTS, int N>
+__device__ __forceinline__ void update_store(const float (&s)[N], const typename FVec<N>::type& wv,
+                                             const typename FVec<N>::type& mv, float* wp, float* mp, float* sp, int k,
+                                             unsigned span_bytes, const Bcast& bc, int64_t e, const KvLaunchArgs& a) {
+    float wn[N], mn[N];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        float wo, mo;
-        sgd_update(s4[c], wv[c], mv[c], a.rescale, a.lr, a.momentum, a.wd, wo, mo);
-        wn[c] = wo; mn[c] = mo; sv[c] = s4[c];
-    }
-    if constexpr (KEEP) store_state<NTS>(sp, k, span_bytes, sv);
-    store_state<NTS>(mp, k, span_bytes, mn);
-    store_state<NTS>(wp, k, span_bytes, wn);
-    bcast4(bc, e, wn);
+    for (int c = 0; c < N; ++c)
+        sgd_update(s[c], lane_get<N>(wv, c), lane_get<N>(mv, c), a.rescale, a.lr, a.momentum, a.wd, wn[c], mn[c]);
+    if constexpr (KEEP) store_state<NTS, N>(sp, k, span_bytes, pack_f32<N>(s));
+    store_state<NTS, N>(mp, k, span_bytes, pack_f32<N>(mn));
+    store_state<NTS, N>(wp, k, span_bytes, pack_f32<N>(wn));
+    bcast_vec<N>(bc, e, wn);
 }
 
-template <bool F16, int WT, bool PAIRWISE, bool KEEP, int U, int NTM>
+template <bool F16, int N, int WT, bool PAIRWISE, bool KEEP, int U, int NTM>
 __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
-    using G = Grad<F16>;
-    using E = typename G::elem;
-    constexpr int NV = G::VEC;
-    constexpr int Q = NV / 4;                // float4 pieces of w / m per gradient vector
-    constexpr int TILE = KV_THREADS * NV * U;
+    using E = typename Grad<F16, N>::elem;
+    using FV = typename FVec<N>::type;
+    constexpr int TILE = KV_THREADS * N * U;
     constexpr bool NT = (NTM & 1) != 0;      // gradient loads
     constexpr bool NTL = (NTM & 2) != 0;     // w, m loads
     constexpr int NTS = NTM & 12;            // store policy of w', m', s
@@ -323,24 +351,35 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
     const int64_t KV_CONST* tiles = (const int64_t KV_CONST*)a.tiles + a.tile_lo * 4;
     const uint64_t KV_CONST* table = (const uint64_t KV_CONST*)a.gptrs;
 
-    const int64_t ntiles = a.tile_hi - a.tile_lo;
-    // The hardware deals consecutive workgroup ids round-robin to the 8 XCDs.  xcd_remap = 1 sends
-    // them to 8 contiguous tile ranges, one per XCD; xcd_remap = G > 1 gives every XCD blocks of G
-    // consecutive tiles (rows of 8 G tiles, block x of a row to XCD x); 0 leaves the tiles dealt
-    // one by one.
-    const int64_t blk = a.xcd_remap == 1 ? (ntiles + 7) >> 3 : a.xcd_remap;
-    const int64_t span = a.xcd_remap ? (ntiles + 8 * blk - 1) / (8 * blk) * (8 * blk) : ntiles;
+    // The hardware deals consecutive workgroup ids round-robin to the 8 XCDs.  xcd_remap = G > 0 gives
+    // every XCD blocks of G consecutive tiles (rows of 8 G tiles, block x of a row to XCD x; G = an
+    // eighth of the launch: eight contiguous ranges); 0 leaves the tiles dealt one by one.  All in
+    // 32-bit unsigned arithmetic (the host keeps a launch below 2^31 tiles), with shifts when G is
+    // a power of two: this runs once per workgroup, and a workgroup may be as small as 256 elements.
+    const uint32_t ntiles = (uint32_t)(a.tile_hi - a.tile_lo);
+    const uint32_t blk = (uint32_t)a.xcd_remap;
+    const uint32_t row_len = 8u * blk;
+    const int blk_shift = a.xcd_shift;                       // log2(G), or -1 if G is not a power of two
+    const uint32_t span = a.xcd_span;                        // ntiles rounded up to whole rows (ntiles if G = 0)
 
-    for (int64_t i = blockIdx.x; i < span; i += gridDim.x) {
-        int64_t t = i;
-        if (a.xcd_remap) {
-            const int64_t row = i / (8 * blk), within = i - row * (8 * blk);
-            t = row * (8 * blk) + (within & 7) * blk + (within >> 3);
+    for (uint32_t i = blockIdx.x; i < span; i += gridDim.x) {
+        uint32_t t = i;
+        if (blk) {
+            uint32_t row_start, within;
+            if (blk_shift >= 0) {
+                within = i & (row_len - 1u);
+                row_start = i - within;
+                t = row_start + ((within & 7u) << blk_shift) + (within >> 3);
+            } else {
+                row_start = i / row_len * row_len;
+                within = i - row_start;
+                t = row_start + (within & 7u) * blk + (within >> 3);
+            }
             if (t >= ntiles) continue;
         }
         struct { int32_t seg, count; int64_t arena_off, seg_off; } td;
         {
-            const int64_t KV_CONST* tw = tiles + t * 4;
+            const int64_t KV_CONST* tw = tiles + (int64_t)t * 4;
             const int64_t w0 = tw[0];
             td.seg = (int32_t)(w0 & 0xFFFFFFFF);
             td.count = (int32_t)(w0 >> 32);
@@ -356,25 +395,22 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
 
         // A full tile lies wholly inside the arena, so its w and m vectors can be requested
         // before the gradient pointers have arrived (they are dropped in the rare case that
-        // the gradient buffers turn out not to be 16-byte aligned).
-        f32x4 w4[U][Q], m4[U][Q];
+        // the gradient buffers turn out not to be aligned to one vector).
+        FV wv[U], mv[U];
         if (full) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int k = (tid + u * KV_THREADS) * NV;
-#pragma unroll
-                for (int q = 0; q < Q; ++q) {
-                    w4[u][q] = load_state<NTL>(wp + k + 4 * q);
-                    m4[u][q] = load_state<NTL>(mp + k + 4 * q);
-                }
+                const int k = (tid + u * KV_THREADS) * N;
+                wv[u] = load_state<NTL, N>(wp + k);
+                mv[u] = load_state<NTL, N>(mp + k);
             }
         }
 
-        // The vector path needs every gradient pointer aligned to one gradient vector (16 bytes of
-        // fp32, 8 bytes of fp16) and every replica pointer to one replica vector (16 or 8 bytes).
+        // The vector path needs every gradient pointer aligned to one gradient vector (N elements)
+        // and every replica pointer to one replica vector.
         uint64_t bits = 0;
         for (int r = 0; r < W; ++r) bits |= gp[r];
-        bool vec_ok = (bits & (uint64_t)(NV * sizeof(E) - 1)) == 0;
+        bool vec_ok = (bits & (uint64_t)(N * sizeof(E) - 1)) == 0;
 
         Bcast bc{nullptr, 0, a.bcast_f16};
         if (a.bcast_n > 0) {
@@ -384,44 +420,37 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
                 bc.n = a.bcast_n;
                 uint64_t rbits = 0;
                 for (int r = 0; r < a.bcast_n; ++r) rbits |= row[r];
-                vec_ok = vec_ok && (rbits & (a.bcast_f16 ? 7u : 15u)) == 0;
+                vec_ok = vec_ok && (rbits & (uint64_t)(N * (a.bcast_f16 ? 2 : 4) - 1)) == 0;
             }
         }
 
         if (vec_ok && full) {
             // every gradient load of every unrolled vector is issued before the first store
-            float s[U][NV];
+            float s[U][N];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t e = td.seg_off + (int64_t)(tid + u * KV_THREADS) * NV;
-                reduce_vec<F16, WT, PAIRWISE, NT>(gp, W, e * (int64_t)sizeof(E), s[u]);
+                const int64_t e = td.seg_off + (int64_t)(tid + u * KV_THREADS) * N;
+                reduce_vec<F16, N, WT, PAIRWISE, NT>(gp, W, e * (int64_t)sizeof(E), s[u]);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int k = (tid + u * KV_THREADS) * NV;
-#pragma unroll
-                for (int q = 0; q < Q; ++q)
-                    update_store4<KEEP, NTS>(&s[u][4 * q], w4[u][q], m4[u][q], wp, mp, sp, k + 4 * q, span_bytes, bc,
-                                             td.seg_off + k + 4 * q, a);
+                const int k = (tid + u * KV_THREADS) * N;
+                update_store<KEEP, NTS, N>(s[u], wv[u], mv[u], wp, mp, sp, k, span_bytes, bc, td.seg_off + k, a);
             }
         } else if (vec_ok) {
-            // ragged tile: whole vectors first, then at most NV-1 single elements
-            const int nvec = td.count / NV;
+            // ragged tile: whole vectors first, then at most N-1 single elements
+            const int nvec = td.count / N;
             for (int v = tid; v < nvec; v += KV_THREADS) {
-                const int k = v * NV;
-                float s[NV];
-                reduce_vec<F16, WT, PAIRWISE, NT>(gp, W, (td.seg_off + k) * (int64_t)sizeof(E), s);
-#pragma unroll
-                for (int q = 0; q < Q; ++q) {
-                    const f32x4 wv = load_state<NTL>(wp + k + 4 * q);
-                    const f32x4 mv = load_state<NTL>(mp + k + 4 * q);
-                    update_store4<KEEP, NTS>(&s[4 * q], wv, mv, wp, mp, sp, k + 4 * q, span_bytes, bc,
-                                             td.seg_off + k + 4 * q, a);
-                }
+                const int k = v * N;
+                float s[N];
+                reduce_vec<F16, N, WT, PAIRWISE, NT>(gp, W, (td.seg_off + k) * (int64_t)sizeof(E), s);
+                const FV w1 = load_state<NTL, N>(wp + k);
+                const FV m1 = load_state<NTL, N>(mp + k);
+                update_store<KEEP, NTS, N>(s, w1, m1, wp, mp, sp, k, span_bytes, bc, td.seg_off + k, a);
             }
-            const int rem = td.count - nvec * NV;
+            const int rem = td.count - nvec * N;
             if (tid < rem) {
-                const int k = nvec * NV + tid;
+                const int k = nvec * N + tid;
                 scalar_element<F16, WT, PAIRWISE, KEEP>(gp, W, td.seg_off + k, k, wp, mp, sp, bc, a);
             }
         } else {
@@ -431,38 +460,44 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
     }
 }
 
-template <bool F16, int WT, bool PAIRWISE, bool KEEP, int U, int NTM>
+template <bool F16, int N, int WT, bool PAIRWISE, bool KEEP, int U, int NTM>
 hipError_t launch_one(const KvLaunchArgs& a, unsigned grid, hipStream_t st) {
-    hipLaunchKernelGGL((kv_fused<F16, WT, PAIRWISE, KEEP, U, NTM>), dim3(grid), dim3(KV_THREADS), 0, st, a);
+    hipLaunchKernelGGL((kv_fused<F16, N, WT, PAIRWISE, KEEP, U, NTM>), dim3(grid), dim3(KV_THREADS), 0, st, a);
     return hipGetLastError();
 }
 
-template <bool F16, int WT, bool PAIRWISE, bool KEEP, int U>
+template <bool F16, int N, int WT, bool PAIRWISE, bool KEEP, int U>
 hipError_t pick_nt(const KvKernelSel& s, const KvLaunchArgs& a, unsigned grid, hipStream_t st) {
     switch (s.nontemporal) {
-        case 0: return launch_one<F16, WT, PAIRWISE, KEEP, U, 0>(a, grid, st);
-        case 1: return launch_one<F16, WT, PAIRWISE, KEEP, U, 1>(a, grid, st);
-        case 5: return launch_one<F16, WT, PAIRWISE, KEEP, U, 5>(a, grid, st);
-        case 9: return launch_one<F16, WT, PAIRWISE, KEEP, U, 9>(a, grid, st);
-        case 13: return launch_one<F16, WT, PAIRWISE, KEEP, U, 13>(a, grid, st);
+        case 0: return launch_one<F16, N, WT, PAIRWISE, KEEP, U, 0>(a, grid, st);
+        case 1: return launch_one<F16, N, WT, PAIRWISE, KEEP, U, 1>(a, grid, st);
+        case 5: return launch_one<F16, N, WT, PAIRWISE, KEEP, U, 5>(a, grid, st);
+        case 9: return launch_one<F16, N, WT, PAIRWISE, KEEP, U, 9>(a, grid, st);
+        case 13: return launch_one<F16, N, WT, PAIRWISE, KEEP, U, 13>(a, grid, st);
         default: return hipErrorInvalidValue;
     }
 }
 
+// (elements per lane, vectors per lane): 4 x {1, 2, 4}, 2 x {1, 2}, 1 x {1, 2, 4}
 template <bool F16, int WT, bool PAIRWISE, bool KEEP>
-hipError_t pick_u(const KvKernelSel& s, const KvLaunchArgs& a, unsigned grid, hipStream_t st) {
-    switch (s.unroll) {
-        case 1: return pick_nt<F16, WT, PAIRWISE, KEEP, 1>(s, a, grid, st);
-        case 2: return pick_nt<F16, WT, PAIRWISE, KEEP, 2>(s, a, grid, st);
-        case 4: return pick_nt<F16, WT, PAIRWISE, KEEP, 4>(s, a, grid, st);
+hipError_t pick_shape(const KvKernelSel& s, const KvLaunchArgs& a, unsigned grid, hipStream_t st) {
+    switch (s.lane_elems * 8 + s.unroll) {
+        case 4 * 8 + 1: return pick_nt<F16, 4, WT, PAIRWISE, KEEP, 1>(s, a, grid, st);
+        case 4 * 8 + 2: return pick_nt<F16, 4, WT, PAIRWISE, KEEP, 2>(s, a, grid, st);
+        case 4 * 8 + 4: return pick_nt<F16, 4, WT, PAIRWISE, KEEP, 4>(s, a, grid, st);
+        case 2 * 8 + 1: return pick_nt<F16, 2, WT, PAIRWISE, KEEP, 1>(s, a, grid, st);
+        case 2 * 8 + 2: return pick_nt<F16, 2, WT, PAIRWISE, KEEP, 2>(s, a, grid, st);
+        case 1 * 8 + 1: return pick_nt<F16, 1, WT, PAIRWISE, KEEP, 1>(s, a, grid, st);
+        case 1 * 8 + 2: return pick_nt<F16, 1, WT, PAIRWISE, KEEP, 2>(s, a, grid, st);
+        case 1 * 8 + 4: return pick_nt<F16, 1, WT, PAIRWISE, KEEP, 4>(s, a, grid, st);
         default: return hipErrorInvalidValue;
     }
 }
 
 template <bool F16, int WT>
 hipError_t pick_order_keep(const KvKernelSel& s, const KvLaunchArgs& a, unsigned grid, hipStream_t st) {
-    if (s.pairwise) return s.keep_sum ? pick_u<F16, WT, true, true>(s, a, grid, st) : pick_u<F16, WT, true, false>(s, a, grid, st);
-    return s.keep_sum ? pick_u<F16, WT, false, true>(s, a, grid, st) : pick_u<F16, WT, false, false>(s, a, grid, st);
+    if (s.pairwise) return s.keep_sum ? pick_shape<F16, WT, true, true>(s, a, grid, st) : pick_shape<F16, WT, true, false>(s, a, grid, st);
+    return s.keep_sum ? pick_shape<F16, WT, false, true>(s, a, grid, st) : pick_shape<F16, WT, false, false>(s, a, grid, st);
 }
 
 }  // namespace

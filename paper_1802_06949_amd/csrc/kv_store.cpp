@@ -54,7 +54,7 @@ struct kv_store {
     unsigned flags = 0;
     kv_sgd_params p{};
     float rescale = 1.0f;
-    int unroll = 2, wg_per_cu = 0, nontemporal = 1, xcd_remap = 0;
+    int unroll = 1, lane_elems = 4, wg_per_cu = 0, nontemporal = 1, xcd_remap = 0;
     int tile_elems = 0;
     hipStream_t stream = nullptr;
     int device = 0;
@@ -241,7 +241,6 @@ int launch_tiles(kv_store* st, int s0, int s1, int64_t tile_lo, int64_t tile_hi,
     a.tile_lo = tile_lo;
     a.tile_hi = tile_hi;
     a.W = st->W;
-    a.xcd_remap = st->xcd_remap;
     a.lr = st->p.lr;
     a.momentum = st->p.momentum;
     a.wd = st->p.wd;
@@ -252,17 +251,27 @@ int launch_tiles(kv_store* st, int s0, int s1, int64_t tile_lo, int64_t tile_hi,
     sel.pairwise = st->p.reduce_order == KV_REDUCE_PAIRWISE;
     sel.keep_sum = (st->flags & KV_FLAG_KEEP_SUM) != 0;
     sel.unroll = st->unroll;
+    sel.lane_elems = st->lane_elems;
     sel.nontemporal = st->nontemporal;
     const int64_t ntiles = tile_hi - tile_lo;
+    if (ntiles >= (1LL << 31) - 8 * 4096) {
+        set_err(st->err, "a launch of %lld tiles is beyond the kernel's 32-bit tile index", (long long)ntiles);
+        return KV_ERR_ARG;
+    }
     int64_t span = ntiles;
+    a.xcd_remap = 0;
+    a.xcd_shift = -1;
     if (st->xcd_remap) {
         // a block never exceeds an eighth of the launch, so a small launch (one key, a small model)
         // does not start workgroups that find no tile
         const int64_t eighth = (ntiles + 7) / 8;
         const int64_t blk = st->xcd_remap == 1 || st->xcd_remap > eighth ? eighth : st->xcd_remap;
         a.xcd_remap = (int32_t)blk;
+        for (int sh = 0; sh < 31; ++sh)
+            if ((1LL << sh) == blk) a.xcd_shift = sh;
         span = (ntiles + 8 * blk - 1) / (8 * blk) * (8 * blk);
     }
+    a.xcd_span = (uint32_t)span;
     int64_t grid = span;
     if (st->wg_per_cu > 0) {
         int64_t cap = (int64_t)st->num_cus * st->wg_per_cu;
@@ -629,22 +638,28 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     // if its stores are left to allocate there; state that cannot fit is better streamed past it.
     const int64_t state_bytes = 2 * st->plan.arena_numel * (int64_t)sizeof(float);
     st->unroll = 1;
+    st->lane_elems = 4;
     st->wg_per_cu = 0;
     st->nontemporal = state_bytes > (256LL << 20) ? 13 : 9;
     st->xcd_remap = 64;
     if (tuning) {
         if (tuning->unroll != 0) st->unroll = tuning->unroll;
+        if (tuning->lane_elems != 0) st->lane_elems = tuning->lane_elems;
         if (tuning->workgroups_per_cu >= 0) st->wg_per_cu = tuning->workgroups_per_cu;
         if (tuning->nontemporal >= 0) st->nontemporal = tuning->nontemporal;
         if (tuning->xcd_remap >= 0) st->xcd_remap = tuning->xcd_remap;
     }
     const int nt = st->nontemporal;
-    if ((st->unroll != 1 && st->unroll != 2 && st->unroll != 4) || !(nt == 0 || nt == 1 || nt == 5 || nt == 9 || nt == 13)) {
-        set_err(g_err, "kv_init: tuning.unroll must be 1, 2 or 4 and tuning.nontemporal one of 0, 1, 5, 9, 13");
+    const int le = st->lane_elems, un = st->unroll;
+    const bool shape_ok = (le == 4 && (un == 1 || un == 2 || un == 4)) || (le == 2 && (un == 1 || un == 2)) ||
+                          (le == 1 && (un == 1 || un == 2 || un == 4));
+    if (!shape_ok || !(nt == 0 || nt == 1 || nt == 5 || nt == 9 || nt == 13)) {
+        set_err(g_err, "kv_init: tuning (lane_elems, unroll) must be one of (4,1) (4,2) (4,4) (2,1) (2,2) (1,1) (1,2) (1,4) "
+                       "and tuning.nontemporal one of 0, 1, 5, 9, 13");
         delete st;
         return KV_ERR_ARG;
     }
-    st->tile_elems = kv_tile_elems(grad_dtype == KV_F16, st->unroll);
+    st->tile_elems = kv_tile_elems(st->lane_elems, st->unroll);
 
 #define KV_INIT_HIP(call)                                                                     \
     do {                                                                                      \

@@ -14,7 +14,7 @@ int main() {
         kv_plan p; int dt = g() % 2;
         if (kv_plan_build(p, K, n.data(), dt, bucket) != KV_OK) { printf("build failed\n"); return 1; }
         std::vector<KvTile> tiles; std::vector<int64_t> ub, sb;
-        int te = kv_tile_elems(dt, 1 << (g() % 3));
+        int te = kv_tile_elems(1 << (g() % 3), 1 << (g() % 3));
         int64_t total_tiles = 0; for (auto x : n) total_tiles += (x + te - 1) / te;
         if (total_tiles < 300000) { kv_plan_tiles(p, te, tiles, ub, sb); if ((int64_t)tiles.size() != total_tiles) { printf("tiles\n"); return 1; } }
         kv_chain c; c.reset(&p); c.descending = g() % 2;

@@ -35,7 +35,7 @@ def _grads(numel, W, dtype, seed, scale=0.01):
 
 
 # Lengths that straddle the vector width, the wavefront, the workgroup and the
-# tile sizes (1024 / 2048 / 4096 elements for unroll 1 / 2 / 4), plus empty keys.
+# tile sizes (256 * lane_elems * unroll elements: 256 ... 4096), plus empty keys.
 RAGGED = [0, 1, 2, 3, 4, 5, 7, 8, 9, 63, 64, 65, 255, 256, 257, 1023, 1024, 1025, 2047, 2048, 2049,
           4095, 4096, 4097, 8191, 8192, 8193, 0, 12289, 20000]
 
@@ -133,18 +133,18 @@ def test_ragged_keys_all_rank_counts(dtype, W, order):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
-@pytest.mark.parametrize("unroll", [1, 2, 4])
+@pytest.mark.parametrize("lane_elems,unroll", [(4, 1), (4, 2), (4, 4), (2, 1), (2, 2), (1, 1), (1, 2), (1, 4)])
 @pytest.mark.parametrize("tuning", [dict(), dict(workgroups_per_cu=1), dict(xcd_remap=0), dict(nontemporal=0), dict(nontemporal=1), dict(nontemporal=5), dict(nontemporal=9), dict(nontemporal=13),
                                     dict(workgroups_per_cu=2, xcd_remap=1), dict(workgroups_per_cu=3, xcd_remap=0), dict(xcd_remap=1),
                                     dict(xcd_remap=7), dict(xcd_remap=3, workgroups_per_cu=1), dict(xcd_remap=4096)])
-def test_tuning_never_changes_a_bit(dtype, unroll, tuning):
+def test_tuning_never_changes_a_bit(dtype, lane_elems, unroll, tuning):
     numel = RAGGED + [70001]
-    pair = Pair(numel, 8, dtype, 64 << 10, lr=0.1, momentum=0.9, wd=1e-4, unroll=unroll, **tuning)
+    pair = Pair(numel, 8, dtype, 64 << 10, lr=0.1, momentum=0.9, wd=1e-4, unroll=unroll, lane_elems=lane_elems, **tuning)
     try:
         pair.set_weights([_rng(2, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
         for t in range(2):
             pair.step(_grads(numel, 8, dtype, 200 + t))
-            pair.compare(f"unroll={unroll} {tuning} step {t}")
+            pair.compare(f"lane_elems={lane_elems} unroll={unroll} {tuning} step {t}")
     finally:
         pair.close()
 
@@ -595,7 +595,8 @@ def test_maximum_rank_count_and_many_keys():
 
 def test_init_rejects_bad_arguments():
     kv = pytest.importorskip("paper_1802_06949_amd")
-    for kwargs in (dict(W=0), dict(W=257), dict(reduce_order=2), dict(unroll=3), dict(nontemporal=2)):
+    for kwargs in (dict(W=0), dict(W=257), dict(reduce_order=2), dict(unroll=3), dict(nontemporal=2), dict(lane_elems=3),
+                   dict(lane_elems=2, unroll=4)):
         args = dict(W=2, lr=0.1)
         args.update(kwargs)
         with pytest.raises(kv.KVError) as e:
