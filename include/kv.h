@@ -111,8 +111,9 @@ typedef struct kv_sgd_params {
  * Launch tuning; pass NULL for defaults.  None of these changes any result bit.
  *   unroll            vectors per thread per rank in one tile: 1, 2 or 4 (0 = default)
  *   lane_elems        consecutive elements per vector, i.e. per thread and load instruction: 1, 2 or 4
- *                     (0 = default); a tile is 256 * lane_elems * unroll elements; (lane_elems, unroll)
- *                     must be one of (4,1) (4,2) (4,4) (2,1) (2,2) (1,1) (1,2) (1,4)
+ *                     (0 = default: chosen from W and the gradient dtype, or 4 if unroll is given); a tile
+ *                     is 256 * lane_elems * unroll elements; (lane_elems, unroll) must be one of
+ *                     (4,1) (4,2) (4,4) (2,1) (2,2) (1,1) (1,2) (1,4)
  *   workgroups_per_cu cap of resident workgroups per compute unit for the grid-stride
  *                     loop over tiles; 0 = one workgroup per tile
  *   nontemporal       cache policy: bit 0 = gradient loads carry the non-temporal hint; plus the policy
@@ -120,7 +121,8 @@ typedef struct kv_sgd_params {
  *                     12 = write through L2 and non-temporal; one of 0, 1, 5, 9, 13; -1 = default (9 if
  *                     w and m together fit the 256 MiB memory-side cache, else 13)
  *   xcd_remap         how tiles are dealt to the 8 XCDs: 0 = one by one, round robin; 1 = eight contiguous
- *                     ranges, one per XCD; G > 1 = blocks of G consecutive tiles per XCD; -1 = default
+ *                     ranges, one per XCD; G > 1 = blocks of G consecutive tiles per XCD; -1 = default (64, or
+ *                     1024 if w and m do not fit the memory-side cache)
  */
 typedef struct kv_tuning {
     int unroll;

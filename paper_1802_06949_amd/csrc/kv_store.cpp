@@ -632,18 +632,34 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     st->stream = static_cast<hipStream_t>(hip_stream);
 
     // Defaults from sweeps on MI355X.  Non-temporal gradient loads keep the streamed gradients
-    // from evicting w and m out of the memory-side cache; giving every XCD blocks of 64 consecutive
+    // from evicting w and m out of the memory-side cache; giving every XCD blocks of consecutive
     // tiles and write-through stores of w', m' are worth a few percent each.
     // State (w and m) that fits the 256 MiB memory-side cache stays resident between iterations
     // if its stores are left to allocate there; state that cannot fit is better streamed past it.
+    // Elements per lane: the memory system is fastest when a lane has about 32 bytes of gradients
+    // (all W ranks of one vector) in flight, i.e. many small workgroups rather than few large
+    // ones; the table holds the measured best width for the rank counts that have a kernel of
+    // their own (ResNet-50-shaped key set), the kernel for any other W does best with 4.
     const int64_t state_bytes = 2 * st->plan.arena_numel * (int64_t)sizeof(float);
+    const bool resident = state_bytes <= (256LL << 20);
+    int lane = 4;
+    {
+        static const int w_built[5] = {2, 4, 8, 16, 32};
+        static const int lane_f32[5] = {4, 2, 1, 1, 1};
+        static const int lane_f16[5] = {4, 4, 2, 4, 1};
+        for (int i = 0; i < 5; ++i)
+            if (W == w_built[i]) lane = grad_dtype == KV_F16 ? lane_f16[i] : lane_f32[i];
+    }
     st->unroll = 1;
-    st->lane_elems = 4;
+    st->lane_elems = lane;
     st->wg_per_cu = 0;
-    st->nontemporal = state_bytes > (256LL << 20) ? 13 : 9;
-    st->xcd_remap = 64;
+    st->nontemporal = resident ? 9 : 13;
+    st->xcd_remap = resident ? 64 : 1024;
     if (tuning) {
-        if (tuning->unroll != 0) st->unroll = tuning->unroll;
+        if (tuning->unroll != 0) {
+            st->unroll = tuning->unroll;
+            st->lane_elems = 4;            // `unroll` alone keeps its meaning of 4-element vectors per lane
+        }
         if (tuning->lane_elems != 0) st->lane_elems = tuning->lane_elems;
         if (tuning->workgroups_per_cu >= 0) st->wg_per_cu = tuning->workgroups_per_cu;
         if (tuning->nontemporal >= 0) st->nontemporal = tuning->nontemporal;
