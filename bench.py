@@ -70,6 +70,7 @@ def parse_args():
                          "warm-up steps) and time replays of the graphs instead of direct launches")
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--lane-elems", type=int, default=0)
+    ap.add_argument("--resident-workgroups", type=int, default=0)
     ap.add_argument("--workgroups-per-cu", type=int, default=-1)
     ap.add_argument("--nontemporal", type=int, default=-1)
     ap.add_argument("--xcd-remap", type=int, default=-1)
@@ -249,7 +250,8 @@ def main() -> int:
 
     store = kv.KVStore(cfg.numel, cfg.W, cfg.grad_dtype, cfg.bucket_bytes, lr=cfg.lr, momentum=cfg.momentum, wd=cfg.wd,
                        keep_sum=False, lazy=args.lazy, unroll=args.unroll, workgroups_per_cu=args.workgroups_per_cu,
-                       nontemporal=args.nontemporal, xcd_remap=args.xcd_remap, lane_elems=args.lane_elems)
+                       nontemporal=args.nontemporal, xcd_remap=args.xcd_remap, lane_elems=args.lane_elems,
+                       resident_workgroups=args.resident_workgroups)
     for k, w in enumerate(weights):
         if w.size:
             store.set_weights(k, torch.from_numpy(w).cuda())

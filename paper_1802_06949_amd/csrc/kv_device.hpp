@@ -30,6 +30,8 @@ struct KvLaunchArgs {
     int32_t xcd_remap;            // G: consecutive tiles per XCD block (0 = tiles dealt one by one)
     int32_t xcd_shift;            // log2(G) if G is a power of two, else -1
     uint32_t xcd_span;            // tiles of the launch rounded up to whole rows of 8 G (the launch's tiles if G = 0)
+    uint32_t lds_pad;             // host side only: bytes of LDS each workgroup reserves and never touches, which
+                                  // caps the workgroups resident on a compute unit (0 = no cap)
     float lr, momentum, wd, rescale;
 };
 

@@ -462,7 +462,7 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
 
 template <bool F16, int N, int WT, bool PAIRWISE, bool KEEP, int U, int NTM>
 hipError_t launch_one(const KvLaunchArgs& a, unsigned grid, hipStream_t st) {
-    hipLaunchKernelGGL((kv_fused<F16, N, WT, PAIRWISE, KEEP, U, NTM>), dim3(grid), dim3(KV_THREADS), 0, st, a);
+    hipLaunchKernelGGL((kv_fused<F16, N, WT, PAIRWISE, KEEP, U, NTM>), dim3(grid), dim3(KV_THREADS), a.lds_pad, st, a);
     return hipGetLastError();
 }
 

@@ -54,7 +54,7 @@ struct kv_store {
     unsigned flags = 0;
     kv_sgd_params p{};
     float rescale = 1.0f;
-    int unroll = 1, lane_elems = 4, wg_per_cu = 0, nontemporal = 1, xcd_remap = 0;
+    int unroll = 1, lane_elems = 4, wg_per_cu = 0, nontemporal = 1, xcd_remap = 0, resident_wgs = 0;
     int tile_elems = 0;
     hipStream_t stream = nullptr;
     int device = 0;
@@ -241,6 +241,8 @@ int launch_tiles(kv_store* st, int s0, int s1, int64_t tile_lo, int64_t tile_hi,
     a.tile_lo = tile_lo;
     a.tile_hi = tile_hi;
     a.W = st->W;
+    // a compute unit has 160 KB of LDS: reserving 160 KB / n per workgroup lets n of them be resident
+    a.lds_pad = st->resident_wgs >= 3 && st->resident_wgs < 8 ? (uint32_t)((160 * 1024) / st->resident_wgs) & ~1023u : 0u;
     a.lr = st->p.lr;
     a.momentum = st->p.momentum;
     a.wd = st->p.wd;
@@ -650,6 +652,11 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
         for (int i = 0; i < 5; ++i)
             if (W == w_built[i]) lane = grad_dtype == KV_F16 ? lane_f16[i] : lane_f32[i];
     }
+    // With 16 or 32 fp32 ranks even one element per lane keeps more bytes in flight per compute
+    // unit than the memory system likes; fewer resident workgroups are worth another 2-3 %.
+    st->resident_wgs = 0;
+    if (grad_dtype == KV_F32 && W == 16) st->resident_wgs = resident ? 5 : 4;
+    if (grad_dtype == KV_F32 && W == 32) st->resident_wgs = 4;
     st->unroll = 1;
     st->lane_elems = lane;
     st->wg_per_cu = 0;
@@ -664,14 +671,16 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
         if (tuning->workgroups_per_cu >= 0) st->wg_per_cu = tuning->workgroups_per_cu;
         if (tuning->nontemporal >= 0) st->nontemporal = tuning->nontemporal;
         if (tuning->xcd_remap >= 0) st->xcd_remap = tuning->xcd_remap;
+        if (tuning->resident_workgroups != 0) st->resident_wgs = tuning->resident_workgroups;
     }
     const int nt = st->nontemporal;
     const int le = st->lane_elems, un = st->unroll;
     const bool shape_ok = (le == 4 && (un == 1 || un == 2 || un == 4)) || (le == 2 && (un == 1 || un == 2)) ||
                           (le == 1 && (un == 1 || un == 2 || un == 4));
-    if (!shape_ok || !(nt == 0 || nt == 1 || nt == 5 || nt == 9 || nt == 13)) {
+    if (!shape_ok || !(nt == 0 || nt == 1 || nt == 5 || nt == 9 || nt == 13) ||
+        !(st->resident_wgs == 0 || (st->resident_wgs >= 3 && st->resident_wgs <= 8))) {
         set_err(g_err, "kv_init: tuning (lane_elems, unroll) must be one of (4,1) (4,2) (4,4) (2,1) (2,2) (1,1) (1,2) (1,4) "
-                       "and tuning.nontemporal one of 0, 1, 5, 9, 13");
+                       "tuning.nontemporal one of 0, 1, 5, 9, 13 and tuning.resident_workgroups 0 or 3..8");
         delete st;
         return KV_ERR_ARG;
     }

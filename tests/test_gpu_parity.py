@@ -136,7 +136,8 @@ def test_ragged_keys_all_rank_counts(dtype, W, order):
 @pytest.mark.parametrize("lane_elems,unroll", [(4, 1), (4, 2), (4, 4), (2, 1), (2, 2), (1, 1), (1, 2), (1, 4)])
 @pytest.mark.parametrize("tuning", [dict(), dict(workgroups_per_cu=1), dict(xcd_remap=0), dict(nontemporal=0), dict(nontemporal=1), dict(nontemporal=5), dict(nontemporal=9), dict(nontemporal=13),
                                     dict(workgroups_per_cu=2, xcd_remap=1), dict(workgroups_per_cu=3, xcd_remap=0), dict(xcd_remap=1),
-                                    dict(xcd_remap=7), dict(xcd_remap=3, workgroups_per_cu=1), dict(xcd_remap=4096)])
+                                    dict(xcd_remap=7), dict(xcd_remap=3, workgroups_per_cu=1), dict(xcd_remap=4096),
+                                    dict(resident_workgroups=3), dict(resident_workgroups=5, xcd_remap=16)])
 def test_tuning_never_changes_a_bit(dtype, lane_elems, unroll, tuning):
     numel = RAGGED + [70001]
     pair = Pair(numel, 8, dtype, 64 << 10, lr=0.1, momentum=0.9, wd=1e-4, unroll=unroll, lane_elems=lane_elems, **tuning)
@@ -596,7 +597,7 @@ def test_maximum_rank_count_and_many_keys():
 def test_init_rejects_bad_arguments():
     kv = pytest.importorskip("paper_1802_06949_amd")
     for kwargs in (dict(W=0), dict(W=257), dict(reduce_order=2), dict(unroll=3), dict(nontemporal=2), dict(lane_elems=3),
-                   dict(lane_elems=2, unroll=4)):
+                   dict(lane_elems=2, unroll=4), dict(resident_workgroups=2), dict(resident_workgroups=9)):
         args = dict(W=2, lr=0.1)
         args.update(kwargs)
         with pytest.raises(kv.KVError) as e:
