@@ -322,8 +322,8 @@ int kv_copy_bytes(void* dev_dst, const void* dev_src, size_t bytes, void* hip_st
  * writes nothing.  With kv_copy_bytes it gives the measured read and copy ceilings of the GPU that the
  * fused kernel's rate is put next to. */
 int kv_read_bytes(const void* dev_src, size_t bytes, void* hip_stream);
-/* Measured ceiling for a MIX of streams, with the fused kernel's access pattern (one workgroup per
- * 4 KB of every stream, all loads in flight before the first store): every lane sums its 16-byte
+/* Measured ceiling for a MIX of streams with 16 bytes per lane and stream (one workgroup per 4 KB
+ * of every stream, all loads in flight before the first store): every lane sums its 16-byte
  * vector of n_read buffers (1, 2, 4, 8, 16 or 32) and stores the sum to each of n_write buffers
  * (0..8).  dev_bufs: host array of n_read + n_write device pointers, read buffers first, each to
  * `bytes` bytes (multiple of 16), 16-byte aligned, none overlapping a written one.  KV_ERR_ARG otherwise. */
