@@ -70,22 +70,26 @@ __global__ void __launch_bounds__(KV_THREADS) kv_busy_copy_kernel(f32x4* __restr
     }
 }
 // Gather of whole keys out of an arena: tile t of the store's tile table is copied to
-// dst[segment of t] + its offset inside the key.  One workgroup per tile.
+// dst[segment of t] + its offset inside the key.  One wavefront per tile (a tile may be as small
+// as 256 elements, one 16-byte vector per lane), four tiles per workgroup.
 __global__ void __launch_bounds__(KV_THREADS) kv_gather_kernel(const KvTile* __restrict__ tiles, int64_t tile_lo,
-                                                               const float* __restrict__ arena,
+                                                               int64_t tile_hi, const float* __restrict__ arena,
                                                                float* const* __restrict__ dst) {
-    const KvTile td = tiles[tile_lo + blockIdx.x];
+    constexpr int WAVES = KV_THREADS / 64;
+    const int64_t t = tile_lo + (int64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
+    if (t >= tile_hi) return;
+    const KvTile td = tiles[t];
     const float* __restrict__ src = arena + td.arena_off;
     float* __restrict__ out = dst[td.seg] + td.seg_off;
-    const int tid = threadIdx.x;
+    const int lane = threadIdx.x & 63;
     if ((reinterpret_cast<uintptr_t>(out) & 15u) == 0) {
         const int nvec = td.count >> 2;
-        for (int v = tid; v < nvec; v += KV_THREADS)
+        for (int v = lane; v < nvec; v += 64)
             reinterpret_cast<f32x4*>(out)[v] = reinterpret_cast<const f32x4*>(src)[v];
-        const int k = (nvec << 2) + tid;
+        const int k = (nvec << 2) + lane;
         if (k < td.count) out[k] = src[k];
     } else {
-        for (int k = tid; k < td.count; k += KV_THREADS) out[k] = src[k];
+        for (int k = lane; k < td.count; k += 64) out[k] = src[k];
     }
 }
 }  // namespace
@@ -93,8 +97,9 @@ __global__ void __launch_bounds__(KV_THREADS) kv_gather_kernel(const KvTile* __r
 hipError_t kv_launch_gather(const KvTile* tiles, int64_t tile_lo, int64_t tile_hi, const float* arena,
                             float* const* dst_table, hipStream_t stream) {
     if (tile_hi <= tile_lo) return hipSuccess;
-    hipLaunchKernelGGL(kv_gather_kernel, dim3((unsigned)(tile_hi - tile_lo)), dim3(KV_THREADS), 0, stream, tiles, tile_lo,
-                       arena, dst_table);
+    constexpr int64_t waves = KV_THREADS / 64;
+    hipLaunchKernelGGL(kv_gather_kernel, dim3((unsigned)((tile_hi - tile_lo + waves - 1) / waves)), dim3(KV_THREADS), 0,
+                       stream, tiles, tile_lo, tile_hi, arena, dst_table);
     return hipGetLastError();
 }
 
