@@ -9,7 +9,9 @@
 // is no LDS staging and no MFMA; what matters is that every lane issues
 // independent loads (N = 1, 2 or 4 consecutive elements per lane and rank; all W ranks, and `U`
 // such vectors per rank, are in flight before the first add) and that a wavefront's 64 lanes cover
-// contiguous memory per load instruction.
+// contiguous memory per load instruction.  On MI355X the memory system is fastest with roughly
+// 80 KB in flight per compute unit in as many small requests as possible: for 8 fp32 ranks that
+// is N = 1, U = 1 (40 bytes per lane, workgroups of 256 elements), not 16-byte vectors.
 //
 // Arithmetic contract (must match bit for bit what the header of the C ABI
 // states): each element is owned by one lane for all W ranks, the ranks are
