@@ -99,6 +99,7 @@ void kv_chain::reset(const kv_plan* p) {
     marked.assign(p->num_keys, 0);
     next_unit = 0;
     pending_keys = 0;
+    launched_keys = 0;
     iteration = 0;
 }
 
@@ -122,12 +123,14 @@ bool kv_chain::next_run(int* first, int* n) {
         pending[ui] = (int)u.keys.size();
         for (int k : u.keys) marked[k] = 0;
         pending_keys -= (int)u.keys.size();
+        launched_keys += (int)u.keys.size();
         ++next_unit;
     }
     *n = next_unit - pos0;
     *first = descending ? U - next_unit : pos0;      // lowest unit of the run
     if (next_unit == U) {
         next_unit = 0;
+        launched_keys = 0;
         ++iteration;
     }
     return true;

@@ -42,7 +42,8 @@ struct kv_chain {
     std::vector<int> pending;        // per unit: keys still missing for its next run
     std::vector<uint8_t> marked;     // per key
     int next_unit = 0;               // position in the launch order (0 = start of an iteration)
-    int pending_keys = 0;
+    int pending_keys = 0;            // marked keys whose unit has not run
+    int launched_keys = 0;           // keys of the units that have run in the iteration in progress
     int64_t iteration = 0;
     bool descending = false;         // launch order runs from the last unit down to unit 0
 

@@ -812,8 +812,10 @@ int kv_push(kv_store* store, int key, const void* const* dev_grads) {
         return rc;
     }
     record_grads(store, key, dev_grads);
-    // lazy stores let single pushes pile up until the whole iteration can go out as one launch
-    if ((store->flags & KV_FLAG_LAZY_LAUNCH) && store->chain.pending_keys < store->plan.num_keys) return KV_OK;
+    // lazy stores let single pushes pile up until the last key of the iteration is in (then everything
+    // that has not run yet goes out as one launch)
+    if ((store->flags & KV_FLAG_LAZY_LAUNCH) &&
+        store->chain.pending_keys + store->chain.launched_keys < store->plan.num_keys) return KV_OK;
     store->capture_launch = captured;
     rc = drain_chain(store);
     store->capture_launch = false;

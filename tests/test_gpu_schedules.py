@@ -142,6 +142,8 @@ def test_lazy_store_merges_single_pushes_into_one_launch():
         for k in range(K):
             if k not in first_unit_keys:
                 pair.gpu.push(k, dev[k])
+        # the last push of the iteration launches the rest itself: it does not wait for a pull or a wait
+        assert pair.gpu.launch_log()[0] == 4 and pair.gpu.launch_log()[1][-1] == (1, U - 1)
         pair.gpu.wait()
         pair.cpu.step(g)
         assert np.array_equal(out.cpu().numpy(), pair.cpu.w[first_unit_keys[0]])

@@ -196,3 +196,40 @@ def test_at_most_seven_buffer_sets_are_held_for_graphs():
             pair.compare("replay of the eighth set after the release")
         finally:
             pair.close()
+
+
+def test_lazy_store_captures_single_pushes_as_one_launch():
+    """KV_FLAG_LAZY_LAUNCH under capture: the single pushes pile up and the last one records ONE launch; a captured
+    pull of a pushed key records what is ready first."""
+    import torch
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        pair = _pair(s, lazy=True)
+        try:
+            K = len(NUMEL)
+            gA = _grads(40)
+            dA = pair.upload(gA)
+            pair.step(gA, dev=dA, mode="each")
+            pair.compare("eager")
+            before = pair.gpu.launch_log(0)[0]
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=s):
+                for k in range(K):
+                    pair.gpu.push(k, dA[k])
+            assert pair.gpu.launch_log(0)[0] - before == 1
+            pulled = torch.zeros(NUMEL[0], dtype=torch.float32, device="cuda")
+            graph2 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph2, stream=s):
+                for k in range(K - 1):
+                    pair.gpu.push(k, dA[k])
+                pair.gpu.pull(0, pulled)                   # launches the units that are complete, then copies
+                pair.gpu.push(K - 1, dA[K - 1])
+            for i, g in enumerate((graph, graph2, graph)):
+                g.replay()
+                pair.cpu.step(gA)
+                pair.gpu.wait()
+                pair.compare(f"replay {i}")
+            # graph2's pull ran before its last push: it saw key 0 as of that replay (two steps ago by now)
+            assert pulled.abs().sum().item() > 0
+        finally:
+            pair.close()
