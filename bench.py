@@ -68,6 +68,8 @@ def parse_args():
     ap.add_argument("--graph", action="store_true",
                     help="record one iteration per gradient set into a HIP graph (on a side stream, after eager "
                          "warm-up steps) and time replays of the graphs instead of direct launches")
+    ap.add_argument("--keep-sum", action="store_true",
+                    help="the kernel also stores the raw fp32 sums (what the paper's pull returns): +4 bytes per element")
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--lane-elems", type=int, default=0)
     ap.add_argument("--resident-workgroups", type=int, default=0)
@@ -249,7 +251,7 @@ def main() -> int:
     t_gen = time.perf_counter() - t_gen
 
     store = kv.KVStore(cfg.numel, cfg.W, cfg.grad_dtype, cfg.bucket_bytes, lr=cfg.lr, momentum=cfg.momentum, wd=cfg.wd,
-                       keep_sum=False, lazy=args.lazy, unroll=args.unroll, workgroups_per_cu=args.workgroups_per_cu,
+                       keep_sum=args.keep_sum, lazy=args.lazy, unroll=args.unroll, workgroups_per_cu=args.workgroups_per_cu,
                        nontemporal=args.nontemporal, xcd_remap=args.xcd_remap, lane_elems=args.lane_elems,
                        resident_workgroups=args.resident_workgroups)
     for k, w in enumerate(weights):
@@ -326,7 +328,7 @@ def main() -> int:
 
     t_step = wall / args.steps
     agg_gbps = N * cfg.W * itemsize / t_step / 1e9
-    alg_bytes_step = cfg.algorithmic_bytes_per_step + bcast_bytes
+    alg_bytes_step = cfg.algorithmic_bytes_per_step + bcast_bytes + (4 * N if args.keep_sum else 0)
     launches_per_step = launches / args.steps
     alg_bytes_launch = alg_bytes_step / max(launches_per_step, 1e-9)
     launch_s = ev_ms * 1e-3 / max(launches, 1)

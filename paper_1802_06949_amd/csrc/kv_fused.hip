@@ -335,7 +335,9 @@ __device__ __forceinline__ void update_store(const float (&s)[N], const typename
 #pragma unroll
     for (int c = 0; c < N; ++c)
         sgd_update(s[c], lane_get<N>(wv, c), lane_get<N>(mv, c), a.rescale, a.lr, a.momentum, a.wd, wn[c], mn[c]);
-    if constexpr (KEEP) store_state<NTS, N>(sp, k, span_bytes, pack_f32<N>(s));
+    // the raw sums are an output stream that no later launch reads: write-through and non-temporal
+    // whatever the policy of w' and m', so that they do not push w and m out of the memory-side cache
+    if constexpr (KEEP) store_state<12, N>(sp, k, span_bytes, pack_f32<N>(s));
     store_state<NTS, N>(mp, k, span_bytes, pack_f32<N>(mn));
     store_state<NTS, N>(wp, k, span_bytes, pack_f32<N>(wn));
     bcast_vec<N>(bc, e, wn);
