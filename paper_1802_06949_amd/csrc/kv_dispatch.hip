@@ -71,7 +71,8 @@ __global__ void __launch_bounds__(KV_THREADS) kv_busy_copy_kernel(f32x4* __restr
 }
 // Gather of whole keys out of an arena: tile t of the store's tile table is copied to
 // dst[segment of t] + its offset inside the key.  One wavefront per tile (a tile may be as small
-// as 256 elements, one 16-byte vector per lane), four tiles per workgroup.
+// as 256 elements, one 16-byte vector per lane), four tiles per workgroup.  The copies are an output
+// stream: non-temporal stores keep them from pushing w and m out of the memory-side cache.
 __global__ void __launch_bounds__(KV_THREADS) kv_gather_kernel(const KvTile* __restrict__ tiles, int64_t tile_lo,
                                                                int64_t tile_hi, const float* __restrict__ arena,
                                                                float* const* __restrict__ dst) {
@@ -85,11 +86,11 @@ __global__ void __launch_bounds__(KV_THREADS) kv_gather_kernel(const KvTile* __r
     if ((reinterpret_cast<uintptr_t>(out) & 15u) == 0) {
         const int nvec = td.count >> 2;
         for (int v = lane; v < nvec; v += 64)
-            reinterpret_cast<f32x4*>(out)[v] = reinterpret_cast<const f32x4*>(src)[v];
+            __builtin_nontemporal_store(reinterpret_cast<const f32x4*>(src)[v], reinterpret_cast<f32x4*>(out) + v);
         const int k = (nvec << 2) + lane;
-        if (k < td.count) out[k] = src[k];
+        if (k < td.count) __builtin_nontemporal_store(src[k], out + k);
     } else {
-        for (int k = lane; k < td.count; k += 64) out[k] = src[k];
+        for (int k = lane; k < td.count; k += 64) __builtin_nontemporal_store(src[k], out + k);
     }
 }
 }  // namespace
