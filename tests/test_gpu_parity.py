@@ -150,6 +150,30 @@ def test_tuning_never_changes_a_bit(dtype, lane_elems, unroll, tuning):
         pair.close()
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_tuning_on_random_key_sets(seed):
+    """Random launch shapes, cache policies, XCD blocks and occupancy caps on random ragged key sets, rank counts with
+    and without a kernel of their own, both dtypes and both orders: never a bit of difference."""
+    r = _rng(900, seed)
+    K = int(r.integers(1, 12))
+    numel = [int(x) for x in r.choice([0, 1, 3, 17, 255, 256, 257, 1000, 1024, 4097, 10000, 33333, 70001], size=K)]
+    W = int(r.choice([1, 2, 3, 4, 5, 8, 13, 16, 32, 40]))
+    dtype = "f16" if r.integers(2) else "f32"
+    lane, unroll = [(4, 1), (4, 2), (4, 4), (2, 1), (2, 2), (1, 1), (1, 2), (1, 4)][int(r.integers(8))]
+    tuning = dict(lane_elems=lane, unroll=unroll, nontemporal=int(r.choice([0, 1, 5, 9, 13])),
+                  xcd_remap=int(r.choice([0, 1, 2, 5, 16, 64, 1000])), resident_workgroups=int(r.choice([0, 3, 4, 6, 8])),
+                  workgroups_per_cu=int(r.choice([0, 0, 1, 2])))
+    pair = Pair(numel, W, dtype, int(r.choice([64, 4096, 1 << 16, 1 << 22])), lr=0.05, momentum=0.8, wd=1e-3,
+                order=int(r.integers(2)), **tuning)
+    try:
+        pair.set_weights([_rng(901, seed, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        for t in range(2):
+            pair.step(_grads(numel, W, dtype, 1000 + 10 * seed + t), mode="each" if t else "list")
+            pair.compare(f"seed {seed} W={W} {dtype} {numel} {tuning} step {t}")
+    finally:
+        pair.close()
+
+
 @pytest.mark.parametrize("dtype,misalign", [("f32", 1), ("f32", 2), ("f32", 3), ("f16", 1), ("f16", 2), ("f16", 4), ("f16", 7)])
 def test_gradient_buffers_not_16_byte_aligned(dtype, misalign):
     """Views into a flat buffer: aligned to the element only, so the single-element path runs."""
