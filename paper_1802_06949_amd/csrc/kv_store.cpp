@@ -641,10 +641,10 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     // Elements per lane: the memory system is fastest when a lane has about 32 bytes of gradients
     // (all W ranks of one vector) in flight, i.e. many small workgroups rather than few large
     // ones; the table holds the measured best width for the rank counts that have a kernel of
-    // their own (ResNet-50-shaped key set), the kernel for any other W does best with 4.
+    // their own (ResNet-50-shaped key set); the kernel for any other W does best with 4, or 2 from 8 to 39 ranks.
     const int64_t state_bytes = 2 * st->plan.arena_numel * (int64_t)sizeof(float);
     const bool resident = state_bytes <= (256LL << 20);
-    int lane = 4;
+    int lane = W >= 8 && W < 40 ? 2 : 4;      // the kernel for any W (it loads four ranks at a time)
     {
         static const int w_built[5] = {2, 4, 8, 16, 32};
         static const int lane_f32[5] = {4, 2, 1, 1, 1};
