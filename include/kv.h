@@ -269,6 +269,11 @@ int kv_weights_ptr(kv_store* store, int key, void** dev_ptr_out);
  * valid while pushes of the key can still launch.
  */
 int kv_set_broadcast(kv_store* store, int key, int n_replicas, void* const* dev_dst /* host [n_replicas] */, int dtype);
+/* The paper's KVStore.init ends with a broadcast of the initial value to every worker: copies the CURRENT
+ * weights of `key` (-1: of every key) to the replicas registered with kv_set_broadcast, in the
+ * replicas' dtype, on the key's stream and in order with its pushes and kv_set_weights.  Keys
+ * without replicas are skipped; KV_ERR_STATE if the key is pushed and waits for its launch. */
+int kv_broadcast_weights(kv_store* store, int key);
 
 /* Makes the store's stream wait (on the GPU, not the host) for hip_event (a hipEvent_t recorded on
  * another stream): the read dependency of later pushes on gradients that the other stream produces. */

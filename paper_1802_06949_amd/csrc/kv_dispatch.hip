@@ -93,7 +93,56 @@ __global__ void __launch_bounds__(KV_THREADS) kv_gather_kernel(const KvTile* __r
         for (int k = lane; k < td.count; k += 64) __builtin_nontemporal_store(src[k], out + k);
     }
 }
+// Copies the current weights of the keys whose tiles are [tile_lo, tile_hi) to their replica buffers
+// (rows of n_rep pointers per segment; a null first pointer: the key has no replicas), as fp32 or rounded
+// to nearest-even fp16.  One wavefront per tile, non-temporal stores (the replicas are output streams).
+__global__ void __launch_bounds__(KV_THREADS) kv_replicate_kernel(const KvTile* __restrict__ tiles, int64_t tile_lo,
+                                                                  int64_t tile_hi, const float* __restrict__ arena,
+                                                                  const void* const* __restrict__ rows, int n_rep,
+                                                                  int rep_f16) {
+    typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+    constexpr int WAVES = KV_THREADS / 64;
+    const int64_t t = tile_lo + (int64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
+    if (t >= tile_hi) return;
+    const KvTile td = tiles[t];
+    const void* const* row = rows + (int64_t)td.seg * n_rep;
+    if (row[0] == nullptr) return;
+    const float* __restrict__ src = arena + td.arena_off;
+    const int lane = threadIdx.x & 63;
+    uintptr_t bits = 0;
+    for (int r = 0; r < n_rep; ++r) bits |= reinterpret_cast<uintptr_t>(row[r]);
+    const bool vec_ok = (bits & (rep_f16 ? 7u : 15u)) == 0;      // seg_off is a multiple of 4 elements
+    const int nvec = vec_ok ? td.count >> 2 : 0;
+    for (int v = lane; v < nvec; v += 64) {
+        const f32x4 x = reinterpret_cast<const f32x4*>(src)[v];
+        if (rep_f16) {
+            f16x4 h;
+            for (int c = 0; c < 4; ++c) h[c] = (_Float16)x[c];
+            for (int r = 0; r < n_rep; ++r)
+                __builtin_nontemporal_store(h, reinterpret_cast<f16x4*>((_Float16*)row[r] + td.seg_off) + v);
+        } else {
+            for (int r = 0; r < n_rep; ++r)
+                __builtin_nontemporal_store(x, reinterpret_cast<f32x4*>((float*)row[r] + td.seg_off) + v);
+        }
+    }
+    for (int k = (nvec << 2) + lane; k < td.count; k += 64) {
+        const float x = src[k];
+        for (int r = 0; r < n_rep; ++r) {
+            if (rep_f16) __builtin_nontemporal_store((_Float16)x, (_Float16*)row[r] + td.seg_off + k);
+            else __builtin_nontemporal_store(x, (float*)row[r] + td.seg_off + k);
+        }
+    }
+}
 }  // namespace
+
+hipError_t kv_launch_replicate(const KvTile* tiles, int64_t tile_lo, int64_t tile_hi, const float* arena,
+                               const void* const* rows, int n_rep, int rep_f16, hipStream_t stream) {
+    if (tile_hi <= tile_lo || n_rep <= 0) return hipSuccess;
+    constexpr int64_t waves = KV_THREADS / 64;
+    hipLaunchKernelGGL(kv_replicate_kernel, dim3((unsigned)((tile_hi - tile_lo + waves - 1) / waves)), dim3(KV_THREADS), 0,
+                       stream, tiles, tile_lo, tile_hi, arena, rows, n_rep, rep_f16);
+    return hipGetLastError();
+}
 
 hipError_t kv_launch_gather(const KvTile* tiles, int64_t tile_lo, int64_t tile_hi, const float* arena,
                             float* const* dst_table, hipStream_t stream) {

@@ -36,3 +36,9 @@ hipError_t kv_launch_read(const void* src, size_t bytes, hipStream_t stream);
 // every lane sums its 16-byte vector of the read buffers and stores the sum to every written buffer.
 // A measured ceiling for a mix of streams.
 hipError_t kv_launch_mix(void* const* bufs, int n_read, int n_write, size_t bytes, hipStream_t stream);
+
+// Copies the current weights of the keys whose tiles are [tile_lo, tile_hi) to their replica buffers:
+// rows is the device table [segments * n_rep] of replica pointers (a null first pointer: none for
+// that key), replicas are fp32 or, with rep_f16, fp16 rounded to nearest even.
+hipError_t kv_launch_replicate(const KvTile* tiles, int64_t tile_lo, int64_t tile_hi, const float* arena,
+                               const void* const* rows, int n_rep, int rep_f16, hipStream_t stream);

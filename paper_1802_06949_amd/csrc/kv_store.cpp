@@ -1032,6 +1032,38 @@ int kv_set_broadcast(kv_store* store, int key, int n_replicas, void* const* dev_
     return KV_OK;
 }
 
+int kv_broadcast_weights(kv_store* store, int key) {
+    if (!store) return KV_ERR_ARG;
+    if (key != -1) {
+        int rc = check_key(store, key);
+        if (rc != KV_OK) return rc;
+    }
+    if (store->bcast_n == 0 || !store->d_bcast) return KV_OK;           // no key has replicas
+    const int k0 = key == -1 ? 0 : key, k1 = key == -1 ? store->plan.num_keys : key + 1;
+    for (int k = k0; k < k1; ++k) {
+        if (store->chain.marked[k]) {
+            set_err(store->err, "kv_broadcast_weights: key %d is pushed and waits for its launch", k);
+            return KV_ERR_STATE;
+        }
+    }
+    if (key == -1 && store->schedule != KV_SCHED_CONCURRENT) {
+        // segments are in arena order: all keys are one contiguous range of tiles
+        const size_t nseg = store->plan.seg_key.size();
+        KV_HIP(store, kv_launch_replicate(store->d_tiles, store->seg_tile_begin[0], store->seg_tile_begin[nseg], store->w,
+                                          store->d_bcast, store->bcast_n, store->bcast_f16, store->stream));
+        return KV_OK;
+    }
+    for (int k = k0; k < k1; ++k) {
+        const int sgm = store->plan.key_seg[k];
+        hipStream_t stream = key_stream(store, k);
+        int rc = fork_to(store, stream, lane_of(store, k));
+        if (rc != KV_OK) return rc;
+        KV_HIP(store, kv_launch_replicate(store->d_tiles, store->seg_tile_begin[sgm], store->seg_tile_begin[sgm + 1],
+                                          store->w, store->d_bcast, store->bcast_n, store->bcast_f16, stream));
+    }
+    return KV_OK;
+}
+
 int kv_release_captures(kv_store* store) {
     if (!store) return KV_ERR_ARG;
     for (int i = 0; i < NSLOT; ++i) store->pinned[i] = false;

@@ -92,6 +92,7 @@ def load_library() -> ctypes.CDLL:
     sig("kv_set_broadcast", c_int, c_vp, c_int, c_int, P(c_vp), c_int)
     sig("kv_set_schedule", c_int, c_vp, c_int, c_int, c_int)
     sig("kv_barrier", c_int, c_vp)
+    sig("kv_broadcast_weights", c_int, c_vp, c_int)
     sig("kv_release_captures", c_int, c_vp)
     sig("kv_store_plan", c_vp, c_vp)
     sig("kv_launch_log", c_int, c_vp, P(c_i64), P(c_int), P(c_int), c_int)
@@ -357,6 +358,10 @@ class KVStore:
         self._check(self._L.kv_set_broadcast(self._h, key, len(ptrs), arr, _dtype_code(dtype)))
         self._bcast_keep = getattr(self, "_bcast_keep", {})
         self._bcast_keep[key] = replicas
+
+    def broadcast_weights(self, key: int = -1) -> None:
+        """kv_broadcast_weights: copies the current weights of a key (-1: all) to its replicas."""
+        self._check(self._L.kv_broadcast_weights(self._h, key))
 
     def set_schedule(self, schedule: int, n_streams: int = 1, outstanding: int = 0) -> None:
         self._check(self._L.kv_set_schedule(self._h, schedule, n_streams, outstanding))

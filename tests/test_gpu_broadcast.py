@@ -66,6 +66,10 @@ def test_replicas_receive_the_updated_weights(grad_dtype, rep_dtype, R, schedule
         reps = _replicas(NUMEL, R, rep_dtype)
         for k in range(len(NUMEL)):
             pair.gpu.set_broadcast(k, reps[k], rep_dtype)
+        # the paper's KVStore.init: every worker receives the initial value
+        pair.gpu.broadcast_weights()
+        pair.gpu.wait()
+        _check(pair, reps, rep_dtype, "initial value")
         for t in range(3):
             pair.step(_grads(NUMEL, W, grad_dtype, 10 + t), mode="list" if t != 1 else "each")
             pair.compare(f"step {t}")
@@ -80,8 +84,13 @@ def test_replicas_that_are_not_16_byte_aligned(rep_dtype, misalign):
     pair = Pair(numel, 2, "f32", 1 << 20, lr=0.1, momentum=0.9, wd=1e-4)
     try:
         reps = _replicas(numel, 2, rep_dtype, misalign)
+        pair.set_weights([_rng(2, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
         for k in range(len(numel)):
             pair.gpu.set_broadcast(k, reps[k], rep_dtype)
+        for k in (3, 1, 0, 2):                       # key by key
+            pair.gpu.broadcast_weights(k)
+        pair.gpu.wait()
+        _check(pair, reps, rep_dtype, "misaligned initial value")
         for t in range(2):
             pair.step(_grads(numel, 2, "f32", 20 + t))
             pair.compare(f"step {t}")
@@ -151,5 +160,36 @@ def test_resnet50_full_size_with_half_replicas():
         pair.step(wl.make_step_gradients(cfg, 0, 16), oracle_threads=8)
         pair.compare("cfg4 + f16 replica")
         _check(pair, reps, "f16", "cfg4")
+    finally:
+        pair.close()
+
+
+def test_broadcast_of_current_weights_skips_keys_without_replicas_and_refuses_pending_keys():
+    import torch
+    numel = [300, 5000, 64]
+    pair = Pair(numel, 2, "f32", 1 << 20, lr=0.1, momentum=0.9, wd=1e-4)
+    try:
+        pair.set_weights([_rng(3, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        pair.gpu.broadcast_weights()                       # no replicas at all: nothing to do
+        reps = _replicas(numel, 2, "f16")
+        pair.gpu.set_broadcast(1, reps[1], "f16")          # only key 1
+        pair.gpu.broadcast_weights()
+        pair.gpu.wait()
+        ref = orc.round_to_half(pair.cpu.w[1])
+        for t in reps[1]:
+            assert np.array_equal(t.cpu().numpy().view(np.uint16), ref.view(np.uint16))
+        for k in (0, 2):
+            for t in reps[k]:
+                assert torch.all(t == 7.0)                 # untouched
+        dev = pair.upload(_grads(numel, 2, "f32", 30))
+        pair.gpu.push(1, dev[1])                           # keys 0..2 share a bucket: key 1 now waits for the others
+        with pytest.raises(pair.kv.KVError) as e:
+            pair.gpu.broadcast_weights(1)
+        assert e.value.status == -3
+        with pytest.raises(pair.kv.KVError):
+            pair.gpu.broadcast_weights(3)
+        pair.gpu.push(0, dev[0])
+        pair.gpu.push(2, dev[2])
+        pair.gpu.wait()
     finally:
         pair.close()
