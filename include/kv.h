@@ -121,7 +121,8 @@ typedef struct kv_sgd_params {
  *                     12 = write through L2 and non-temporal; one of 0, 1, 5, 9, 13; -1 = default (9 if
  *                     w and m together fit the 256 MiB memory-side cache, else 13)
  *   resident_workgroups  cap of workgroups resident per compute unit, 3..8 (8 = the hardware's own limit),
- *                     enforced by reserving LDS; 0 = default (a cap only for 16 or 32 fp32 ranks).  Unlike
+ *                     enforced by reserving LDS; 0 = default (a cap for 16 or 32 fp32 ranks, and for most rank
+ *                     counts when w and m do not fit the memory-side cache).  Unlike
  *                     workgroups_per_cu the grid still has one workgroup per tile.
  *   xcd_remap         how tiles are dealt to the 8 XCDs: 0 = one by one, round robin; 1 = eight contiguous
  *                     ranges, one per XCD; G > 1 = blocks of G consecutive tiles per XCD; -1 = default (64, or

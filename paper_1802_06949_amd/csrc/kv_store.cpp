@@ -653,10 +653,18 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
             if (W == w_built[i]) lane = grad_dtype == KV_F16 ? lane_f16[i] : lane_f32[i];
     }
     // With 16 or 32 fp32 ranks even one element per lane keeps more bytes in flight per compute
-    // unit than the memory system likes; fewer resident workgroups are worth another 2-3 %.
+    // unit than the memory system likes; fewer resident workgroups are worth another 2-3 %.  When
+    // the state does not fit the memory-side cache a cap pays for every rank count (3-8 %; measured
+    // on the VGG-16-shaped key set); with resident state and few ranks it costs.
     st->resident_wgs = 0;
-    if (grad_dtype == KV_F32 && W == 16) st->resident_wgs = resident ? 5 : 4;
-    if (grad_dtype == KV_F32 && W == 32) st->resident_wgs = 4;
+    if (grad_dtype == KV_F32) {
+        if (W == 16) st->resident_wgs = resident ? 5 : 4;
+        if (W == 32) st->resident_wgs = 4;
+        if (!resident && W == 2) st->resident_wgs = 5;
+        if (!resident && (W == 4 || W == 8)) st->resident_wgs = 6;
+    } else if (!resident && W == 16) {
+        st->resident_wgs = 5;
+    }
     st->unroll = 1;
     st->lane_elems = lane;
     st->wg_per_cu = 0;
