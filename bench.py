@@ -68,6 +68,9 @@ def parse_args():
     ap.add_argument("--graph", action="store_true",
                     help="record one iteration per gradient set into a HIP graph (on a side stream, after eager "
                          "warm-up steps) and time replays of the graphs instead of direct launches")
+    ap.add_argument("--autotune", action="store_true",
+                    help="KV_FLAG_AUTOTUNE: the store tries launch shapes during (at least 45) warm-up steps and keeps "
+                         "the fastest; the chosen tuning is reported in config.tuning")
     ap.add_argument("--keep-sum", action="store_true",
                     help="the kernel also stores the raw fp32 sums (what the paper's pull returns): +4 bytes per element")
     ap.add_argument("--unroll", type=int, default=0)
@@ -253,7 +256,7 @@ def main() -> int:
     store = kv.KVStore(cfg.numel, cfg.W, cfg.grad_dtype, cfg.bucket_bytes, lr=cfg.lr, momentum=cfg.momentum, wd=cfg.wd,
                        keep_sum=args.keep_sum, lazy=args.lazy, unroll=args.unroll, workgroups_per_cu=args.workgroups_per_cu,
                        nontemporal=args.nontemporal, xcd_remap=args.xcd_remap, lane_elems=args.lane_elems,
-                       resident_workgroups=args.resident_workgroups)
+                       resident_workgroups=args.resident_workgroups, autotune=args.autotune)
     for k, w in enumerate(weights):
         if w.size:
             store.set_weights(k, torch.from_numpy(w).cuda())
@@ -285,7 +288,7 @@ def main() -> int:
         def do_step(i):
             store.push_list(lists[i % nsets])
 
-    for i in range(max(args.warmup, nsets if args.graph else 0)):
+    for i in range(max(args.warmup, nsets if args.graph else 0, 45 if args.autotune else 0)):
         do_step(i)
     store.wait()
     torch.cuda.synchronize()
@@ -423,6 +426,7 @@ def main() -> int:
             "units": store.plan.num_units,
             "launches_per_step": launches_per_step,
             "push_mode": args.push_mode + (", replayed from HIP graphs" if args.graph else ""),
+            "tuning": dict(store.get_tuning()[0], self_tuned=args.autotune, settled=store.get_tuning()[1]),
             "schedule": args.schedule + (f" ({args.streams} streams, barrier every {args.outstanding} keys)"
                                          if args.schedule == "concurrent" else ""),
             "pull": "zero-copy (weights read in place in the arena)" if args.broadcast == "none" else

@@ -66,12 +66,20 @@ enum kv_flags { KV_FLAG_KEEP_SUM   = 1u,                  /* also store s (kv_pu
                                                              order in which a backward pass produces gradients
                                                              (last layer first).  Still a function of the key
                                                              set alone, so the same on every worker. */
-                KV_FLAG_LAZY_LAUNCH = 4u };               /* a single kv_push launches nothing until every key
+                KV_FLAG_LAZY_LAUNCH = 4u,               /* a single kv_push launches nothing until every key
                                                              of the iteration is pushed (then all units go out
                                                              as ONE launch), or until a pull, wait or barrier
                                                              asks for what is ready: the paper's Dependency
                                                              Chaining loop, which issues all pushes before the
                                                              first pull */
+                KV_FLAG_AUTOTUNE = 8u };                  /* the store tunes its launch shape while it runs: every
+                                                             shape computes the same bits, so the first ~35
+                                                             launches that cover the whole key set (list pushes of
+                                                             all keys, or a lazy store) each try another lane
+                                                             width, cap of resident workgroups or XCD block, timed
+                                                             with events; the fastest is kept (kv_get_tuning).  Each
+                                                             trial waits for the previous launch on the host.
+                                                             Needs unroll = 1; never runs inside a graph capture */
 
 /*
  * The paper's three ways of embedding the aggregation into the worker's task flow
@@ -237,6 +245,9 @@ int kv_push_list(kv_store* store, int nkeys, const int* keys /* host */, const v
  * log and the launch counter count a captured launch once, when it is recorded.
  */
 int kv_release_captures(kv_store* store);
+/* The launch tuning in force (the defaults resolved, or what KV_FLAG_AUTOTUNE has chosen so far);
+ * *tuning_done_out (may be NULL) is 0 while a store that tunes itself is still trying shapes. */
+int kv_get_tuning(const kv_store* store, kv_tuning* tuning_out /* host */, int* tuning_done_out /* host */);
 
 /*
  * kv_pull: copies the key's current weights (numel fp32) to dev_out on the store's

@@ -39,6 +39,31 @@ constexpr int NSLOT = 8;    // cached device pointer tables
 constexpr int NSTAGE = 8;   // pinned staging chunks in flight
 constexpr int LOG_CAP = 4096;
 
+// One cut of the key set into tiles (depends on the elements per tile): the device table, the first
+// tile of every unit and of every segment (tiles of segment g: [seg_tile_begin[g], seg_tile_begin[g + 1])).
+struct TileSet {
+    KvTile* d_tiles = nullptr;
+    std::vector<int64_t> unit_tile_begin, seg_tile_begin;
+};
+
+// Online tuning (KV_FLAG_AUTOTUNE): every launch shape computes the same bits, so the first
+// iterations of a training run can each try another one.  A candidate is timed with a pair of
+// events around launches that cover the whole key set; the fastest one is kept.
+struct Candidate {
+    int lane, cap, xcd;
+};
+struct Tuner {
+    bool active = false;
+    int phase = 0;                       // 0: lane width x occupancy cap, 1: XCD block, 2: done
+    std::vector<Candidate> cands;
+    std::vector<float> best_ms;
+    size_t idx = 0;
+    int rep = 0;
+    bool pending = false;                // a timed launch is in flight
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+};
+constexpr int TUNE_REPS = 2;
+
 struct Deferred {
     int key;
     void* dst;
@@ -63,8 +88,11 @@ struct kv_store {
     float* w = nullptr;
     float* m = nullptr;
     float* s = nullptr;
-    KvTile* d_tiles = nullptr;
-    std::vector<int64_t> unit_tile_begin;
+    // Tile tables, indexed by log2(lane_elems); only the one in use exists unless the store tunes
+    // itself (KV_FLAG_AUTOTUNE).  ts is the one in use.
+    TileSet sets[3];
+    TileSet* ts = nullptr;
+    Tuner tuner;
 
     size_t table_elems = 0;                       // num_segs * W
     std::vector<const void*> cur_ptrs;            // host: pointers of the pushes not yet launched
@@ -103,7 +131,6 @@ struct kv_store {
     bool in_list = false;                         // inside kv_push_list: one fork event serves the whole list
     bool list_forked = false;
     std::vector<uint8_t> lane_waited;             // per lane: already waits for this list's fork event
-    std::vector<int64_t> seg_tile_begin;          // tiles of segment sgm: [seg_tile_begin[sgm], seg_tile_begin[sgm + 1])
 
     std::vector<std::pair<int, int>> log;
     int64_t launches_total = 0;
@@ -133,7 +160,10 @@ void free_store(kv_store* st) {
     if (st->w) (void)hipFree(st->w);
     if (st->m) (void)hipFree(st->m);
     if (st->s) (void)hipFree(st->s);
-    if (st->d_tiles) (void)hipFree(st->d_tiles);
+    for (TileSet& t : st->sets)
+        if (t.d_tiles) (void)hipFree(t.d_tiles);
+    if (st->tuner.e0) (void)hipEventDestroy(st->tuner.e0);
+    if (st->tuner.e1) (void)hipEventDestroy(st->tuner.e1);
     for (int i = 0; i < NSLOT; ++i)
         if (st->d_slot[i]) (void)hipFree(st->d_slot[i]);
     if (st->d_bcast) (void)hipFree(st->d_bcast);
@@ -230,7 +260,7 @@ int launch_tiles(kv_store* st, int s0, int s1, int64_t tile_lo, int64_t tile_hi,
     int rc = table_for(st, s0, s1, stream, &table);
     if (rc != KV_OK) return rc;
     KvLaunchArgs a{};
-    a.tiles = st->d_tiles;
+    a.tiles = st->ts->d_tiles;
     a.gptrs = table;
     a.w = st->w;
     a.m = st->m;
@@ -289,11 +319,78 @@ int launch_tiles(kv_store* st, int s0, int s1, int64_t tile_lo, int64_t tile_hi,
 }
 
 // Launches units [first, first + n) as one kernel, then the pulls queued on them.
+void tuner_apply(kv_store* st, const Candidate& c) {
+    st->lane_elems = c.lane;
+    st->unroll = 1;
+    st->tile_elems = kv_tile_elems(c.lane, 1);
+    st->ts = &st->sets[c.lane == 1 ? 0 : c.lane == 2 ? 1 : 2];
+    st->resident_wgs = c.cap;
+    st->xcd_remap = c.xcd;
+}
+
+// Called before a launch that covers the whole key set: books the time of the previous timed launch,
+// moves on to the next candidate (or locks in the fastest one) and applies it.
+int tuner_step(kv_store* st) {
+    Tuner& t = st->tuner;
+    if (t.pending) {
+        float ms = 0.0f;
+        KV_HIP(st, hipEventSynchronize(t.e1));
+        KV_HIP(st, hipEventElapsedTime(&ms, t.e0, t.e1));
+        t.pending = false;
+        if (ms < t.best_ms[t.idx]) t.best_ms[t.idx] = ms;
+        if (++t.rep >= TUNE_REPS) {
+            t.rep = 0;
+            ++t.idx;
+        }
+    }
+    if (t.idx >= t.cands.size()) {
+        size_t best = 0;
+        for (size_t i = 1; i < t.cands.size(); ++i)
+            if (t.best_ms[i] < t.best_ms[best]) best = i;
+        const Candidate win = t.cands[best];
+        const float win_ms = t.best_ms[best];
+        if (t.phase == 0) {
+            // phase 1: XCD block sizes around the default, for the winning lane width and cap
+            t.phase = 1;
+            t.cands.clear();                    // capacity stays: no allocation here
+            t.best_ms.clear();
+            t.cands.push_back(win);
+            t.best_ms.push_back(win_ms);
+            for (int xcd : {16, 64, 256, 1024})
+                if (xcd != win.xcd) {
+                    t.cands.push_back(Candidate{win.lane, win.cap, xcd});
+                    t.best_ms.push_back(1e30f);
+                }
+            t.idx = 1;
+        } else {
+            t.phase = 2;
+            t.active = false;
+            tuner_apply(st, win);
+            return KV_OK;
+        }
+    }
+    tuner_apply(st, t.cands[t.idx]);
+    return KV_OK;
+}
+
 int launch_run(kv_store* st, int first, int n) {
     const int s0 = st->plan.units[first].seg_begin;
     const int s1 = st->plan.units[first + n - 1].seg_end;
-    int rc = launch_tiles(st, s0, s1, st->unit_tile_begin[first], st->unit_tile_begin[first + n], st->stream, first, n);
+    // a store that tunes itself times the launches that cover the whole key set (never inside a capture)
+    const bool timed = st->tuner.active && first == 0 && n == (int)st->plan.units.size() && !st->capture_launch &&
+                       !st->capture_iteration;
+    if (timed) {
+        int rc = tuner_step(st);
+        if (rc != KV_OK) return rc;
+    }
+    const bool record = timed && st->tuner.active;
+    if (record) KV_HIP(st, hipEventRecord(st->tuner.e0, st->stream));
+    int rc = launch_tiles(st, s0, s1, st->ts->unit_tile_begin[first], st->ts->unit_tile_begin[first + n], st->stream, first, n);
     if (rc != KV_OK) return rc;
+    if (record) {
+        KV_HIP(st, hipEventRecord(st->tuner.e1, st->stream));
+        st->tuner.pending = true;
+    }
     for (int u = first; u < first + n; ++u) {
         for (const Deferred& d : st->deferred[u]) {
             rc = issue_copy_out(st, d.key, d.dst, d.what, st->stream);
@@ -351,7 +448,7 @@ int launch_key(kv_store* st, int key) {
     hipStream_t stream = key_stream(st, key);
     int rc = fork_to(st, stream, lane_of(st, key));
     if (rc != KV_OK) return rc;
-    rc = launch_tiles(st, sgm, sgm + 1, st->seg_tile_begin[sgm], st->seg_tile_begin[sgm + 1], stream, key, 0);
+    rc = launch_tiles(st, sgm, sgm + 1, st->ts->seg_tile_begin[sgm], st->ts->seg_tile_begin[sgm + 1], stream, key, 0);
     if (rc != KV_OK) return rc;
     if (st->schedule == KV_SCHED_FUNNEL) {
         // the issuing thread does the aggregation itself: nothing else is started before it is done
@@ -608,7 +705,7 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
         return KV_ERR_ARG;
     }
     *out = nullptr;
-    if (!params || W < 1 || W > KV_MAX_W || (flags & ~(unsigned)(KV_FLAG_KEEP_SUM | KV_FLAG_DESCENDING | KV_FLAG_LAZY_LAUNCH))) {
+    if (!params || W < 1 || W > KV_MAX_W || (flags & ~(unsigned)(KV_FLAG_KEEP_SUM | KV_FLAG_DESCENDING | KV_FLAG_LAZY_LAUNCH | KV_FLAG_AUTOTUNE))) {
         set_err(g_err, "kv_init: bad arguments (params=%p, W=%d, flags=%u)", (const void*)params, W, flags);
         return KV_ERR_ARG;
     }
@@ -692,6 +789,11 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
         delete st;
         return KV_ERR_ARG;
     }
+    if ((flags & KV_FLAG_AUTOTUNE) && st->unroll != 1) {
+        set_err(g_err, "kv_init: KV_FLAG_AUTOTUNE tunes shapes with unroll = 1 only");
+        delete st;
+        return KV_ERR_ARG;
+    }
     st->tile_elems = kv_tile_elems(st->lane_elems, st->unroll);
 
 #define KV_INIT_HIP(call)                                                                     \
@@ -709,9 +811,16 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     KV_INIT_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, st->device));
     if (cus > 0) st->num_cus = cus;
 
-    std::vector<KvTile> tiles;
+    // tile tables: the one of the chosen shape, or one per lane width for a store that tunes itself
+    std::vector<KvTile> tiles[3];
+    const bool autotune = (flags & KV_FLAG_AUTOTUNE) != 0;
+    const int lane_idx = st->lane_elems == 1 ? 0 : st->lane_elems == 2 ? 1 : 2;
+    st->ts = &st->sets[lane_idx];
     try {
-        kv_plan_tiles(st->plan, st->tile_elems, tiles, st->unit_tile_begin, st->seg_tile_begin);
+        for (int i = 0; i < 3; ++i) {
+            if (i == lane_idx) kv_plan_tiles(st->plan, st->tile_elems, tiles[i], st->sets[i].unit_tile_begin, st->sets[i].seg_tile_begin);
+            else if (autotune) kv_plan_tiles(st->plan, kv_tile_elems(1 << i, 1), tiles[i], st->sets[i].unit_tile_begin, st->sets[i].seg_tile_begin);
+        }
         st->table_elems = st->plan.seg_key.size() * (size_t)W;
         st->cur_ptrs.assign(st->table_elems, nullptr);
         for (int i = 0; i < NSLOT; ++i) {
@@ -735,10 +844,29 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
         KV_INIT_HIP(hipMalloc((void**)&st->s, arena_bytes));
         KV_INIT_HIP(hipMemsetAsync(st->s, 0, arena_bytes, st->stream));
     }
-    const size_t tile_bytes = (tiles.empty() ? 1 : tiles.size()) * sizeof(KvTile);
-    KV_INIT_HIP(hipMalloc((void**)&st->d_tiles, tile_bytes));
-    if (!tiles.empty())
-        KV_INIT_HIP(hipMemcpyAsync(st->d_tiles, tiles.data(), tiles.size() * sizeof(KvTile), hipMemcpyHostToDevice, st->stream));
+    for (int i = 0; i < 3; ++i) {
+        if (i != lane_idx && !autotune) continue;
+        const size_t tile_bytes = (tiles[i].empty() ? 1 : tiles[i].size()) * sizeof(KvTile);
+        KV_INIT_HIP(hipMalloc((void**)&st->sets[i].d_tiles, tile_bytes));
+        if (!tiles[i].empty())
+            KV_INIT_HIP(hipMemcpyAsync(st->sets[i].d_tiles, tiles[i].data(), tiles[i].size() * sizeof(KvTile), hipMemcpyHostToDevice,
+                                       st->stream));
+    }
+    if (autotune) {
+        KV_INIT_HIP(hipEventCreate(&st->tuner.e0));
+        KV_INIT_HIP(hipEventCreate(&st->tuner.e1));
+        try {
+            // phase 0: lane width x cap of resident workgroups (8 = the hardware's own limit), at the default XCD block
+            for (int lane : {1, 2, 4})
+                for (int cap : {8, 6, 5, 4}) st->tuner.cands.push_back(Candidate{lane, cap, st->xcd_remap});
+            st->tuner.best_ms.assign(st->tuner.cands.size(), 1e30f);
+        } catch (const std::bad_alloc&) {
+            set_err(g_err, "kv_init: out of host memory");
+            free_store(st);
+            return KV_ERR_NOMEM;
+        }
+        st->tuner.active = true;
+    }
     for (int i = 0; i < NSLOT; ++i) KV_INIT_HIP(hipMalloc((void**)&st->d_slot[i], st->table_elems * sizeof(void*)));
     KV_INIT_HIP(hipMalloc((void**)&st->d_gather, st->plan.seg_key.size() * sizeof(float*)));
     KV_INIT_HIP(hipHostMalloc((void**)&st->h_stage, (size_t)NSTAGE * st->table_elems * sizeof(void*), hipHostMallocDefault));
@@ -747,7 +875,7 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     KV_INIT_HIP(hipEventCreateWithFlags(&st->join_ev, hipEventDisableTiming));
     KV_INIT_HIP(hipEventCreate(&st->t0));
     KV_INIT_HIP(hipEventCreate(&st->t1));
-    // the host vector `tiles` dies at return: wait for its upload
+    // the host vectors `tiles` die at return: wait for their upload
     KV_INIT_HIP(hipStreamSynchronize(st->stream));
 #undef KV_INIT_HIP
     *out = st;
@@ -940,7 +1068,7 @@ int kv_pull_list(kv_store* store, int nkeys, const int* keys, void* const* dev_o
         if (!want[a]) { ++a; continue; }
         size_t b = a;
         while (b < nseg && want[b]) ++b;
-        KV_HIP(store, kv_launch_gather(store->d_tiles, store->seg_tile_begin[a], store->seg_tile_begin[b], store->w,
+        KV_HIP(store, kv_launch_gather(store->ts->d_tiles, store->ts->seg_tile_begin[a], store->ts->seg_tile_begin[b], store->w,
                                        store->d_gather, store->stream));
         a = b;
     }
@@ -1057,7 +1185,7 @@ int kv_broadcast_weights(kv_store* store, int key) {
     if (key == -1 && store->schedule != KV_SCHED_CONCURRENT) {
         // segments are in arena order: all keys are one contiguous range of tiles
         const size_t nseg = store->plan.seg_key.size();
-        KV_HIP(store, kv_launch_replicate(store->d_tiles, store->seg_tile_begin[0], store->seg_tile_begin[nseg], store->w,
+        KV_HIP(store, kv_launch_replicate(store->ts->d_tiles, store->ts->seg_tile_begin[0], store->ts->seg_tile_begin[nseg], store->w,
                                           store->d_bcast, store->bcast_n, store->bcast_f16, store->stream));
         return KV_OK;
     }
@@ -1066,9 +1194,21 @@ int kv_broadcast_weights(kv_store* store, int key) {
         hipStream_t stream = key_stream(store, k);
         int rc = fork_to(store, stream, lane_of(store, k));
         if (rc != KV_OK) return rc;
-        KV_HIP(store, kv_launch_replicate(store->d_tiles, store->seg_tile_begin[sgm], store->seg_tile_begin[sgm + 1],
+        KV_HIP(store, kv_launch_replicate(store->ts->d_tiles, store->ts->seg_tile_begin[sgm], store->ts->seg_tile_begin[sgm + 1],
                                           store->w, store->d_bcast, store->bcast_n, store->bcast_f16, stream));
     }
+    return KV_OK;
+}
+
+int kv_get_tuning(const kv_store* store, kv_tuning* tuning_out, int* tuning_done_out) {
+    if (!store || !tuning_out) return KV_ERR_ARG;
+    tuning_out->unroll = store->unroll;
+    tuning_out->workgroups_per_cu = store->wg_per_cu;
+    tuning_out->nontemporal = store->nontemporal;
+    tuning_out->xcd_remap = store->xcd_remap;
+    tuning_out->lane_elems = store->lane_elems;
+    tuning_out->resident_workgroups = store->resident_wgs;
+    if (tuning_done_out) *tuning_done_out = store->tuner.active ? 0 : 1;
     return KV_OK;
 }
 

@@ -15,6 +15,7 @@ KV_REDUCE_SEQUENTIAL, KV_REDUCE_PAIRWISE = 0, 1
 KV_FLAG_KEEP_SUM = 1
 KV_FLAG_DESCENDING = 2
 KV_FLAG_LAZY_LAUNCH = 4
+KV_FLAG_AUTOTUNE = 8
 KV_SCHED_CHAINED, KV_SCHED_FUNNEL, KV_SCHED_CONCURRENT = 0, 1, 2
 STATUS = {0: "KV_OK", -1: "KV_ERR_ARG", -2: "KV_ERR_KEY", -3: "KV_ERR_STATE", -4: "KV_ERR_ALIGN",
           -5: "KV_ERR_INCOMPLETE", -6: "KV_ERR_HIP", -7: "KV_ERR_NOMEM"}
@@ -92,6 +93,7 @@ def load_library() -> ctypes.CDLL:
     sig("kv_set_broadcast", c_int, c_vp, c_int, c_int, P(c_vp), c_int)
     sig("kv_set_schedule", c_int, c_vp, c_int, c_int, c_int)
     sig("kv_barrier", c_int, c_vp)
+    sig("kv_get_tuning", c_int, c_vp, P(_Tuning), P(c_int))
     sig("kv_broadcast_weights", c_int, c_vp, c_int)
     sig("kv_release_captures", c_int, c_vp)
     sig("kv_store_plan", c_vp, c_vp)
@@ -243,7 +245,7 @@ class KVStore:
                  reduce_order: int = KV_REDUCE_SEQUENTIAL, keep_sum: bool = False, descending: bool = False, lazy: bool = False,
                  stream: Optional[int] = None,
                  unroll: int = 0, workgroups_per_cu: int = -1, nontemporal: int = -1, xcd_remap: int = -1,
-                 lane_elems: int = 0, resident_workgroups: int = 0):
+                 lane_elems: int = 0, resident_workgroups: int = 0, autotune: bool = False):
         self._L = load_library()
         self._h = None
         self.key_numel = [int(x) for x in key_numel]
@@ -260,7 +262,7 @@ class KVStore:
         h = ctypes.c_void_p()
         rc = self._L.kv_init(ctypes.byref(h), n, arr, self.grad_dtype, self.W, int(bucket_bytes), ctypes.byref(p),
                              (KV_FLAG_KEEP_SUM if keep_sum else 0) | (KV_FLAG_DESCENDING if descending else 0) |
-                             (KV_FLAG_LAZY_LAUNCH if lazy else 0),
+                             (KV_FLAG_LAZY_LAUNCH if lazy else 0) | (KV_FLAG_AUTOTUNE if autotune else 0),
                              ctypes.byref(t), ctypes.c_void_p(self.stream))
         if rc != 0:
             raise KVError(rc, _global_error(self._L))
@@ -319,6 +321,12 @@ class KVStore:
 
     def push_list(self, pl: PushList) -> None:
         self._check(self._L.kv_push_list(self._h, pl.n, pl.keys, pl.ptrs))
+
+    def get_tuning(self) -> Tuple[dict, bool]:
+        """kv_get_tuning: the launch tuning in force and whether a self-tuning store has settled."""
+        t, done = _Tuning(), ctypes.c_int()
+        self._check(self._L.kv_get_tuning(self._h, ctypes.byref(t), ctypes.byref(done)))
+        return {name: getattr(t, name) for name, _ in _Tuning._fields_}, bool(done.value)
 
     def release_captures(self) -> None:
         """Lets the pointer tables that captured launches read be reused (call once the graphs are gone)."""

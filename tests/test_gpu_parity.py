@@ -150,6 +150,32 @@ def test_tuning_never_changes_a_bit(dtype, lane_elems, unroll, tuning):
         pair.close()
 
 
+@pytest.mark.parametrize("dtype,W,lazy", [("f32", 8, False), ("f16", 32, False), ("f32", 3, True)])
+def test_store_that_tunes_itself_never_changes_a_bit(dtype, W, lazy):
+    """KV_FLAG_AUTOTUNE: the first launches each try another launch shape; every step still matches the oracle, and
+    the store settles on one of the shapes it tried."""
+    numel = RAGGED + [70001, 300000]
+    pair = Pair(numel, W, dtype, 64 << 10, lr=0.1, momentum=0.9, wd=1e-4, autotune=True, lazy=lazy, keep_sum=False)
+    try:
+        pair.set_weights([_rng(4, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        sets = [_grads(numel, W, dtype, 400 + j) for j in range(2)]
+        dev = [pair.upload(g) for g in sets]
+        seen, done = set(), False
+        for t in range(48):
+            tuning, done = pair.gpu.get_tuning()
+            seen.add((tuning["lane_elems"], tuning["resident_workgroups"], tuning["xcd_remap"]))
+            pair.step(sets[t % 2], dev=dev[t % 2], mode="each" if lazy else "list")
+            if t % 6 == 0 or t > 40:
+                pair.compare(f"self-tuning step {t}")
+        pair.compare("after tuning")
+        tuning, done = pair.gpu.get_tuning()
+        assert done and len(seen) >= 12                      # 12 lane x cap candidates, then XCD blocks
+        assert tuning["lane_elems"] in (1, 2, 4) and tuning["unroll"] == 1 and tuning["resident_workgroups"] in (4, 5, 6, 8)
+        assert (tuning["lane_elems"], tuning["resident_workgroups"], tuning["xcd_remap"]) in seen
+    finally:
+        pair.close()
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_random_tuning_on_random_key_sets(seed):
     """Random launch shapes, cache policies, XCD blocks and occupancy caps on random ragged key sets, rank counts with
@@ -621,7 +647,8 @@ def test_maximum_rank_count_and_many_keys():
 def test_init_rejects_bad_arguments():
     kv = pytest.importorskip("paper_1802_06949_amd")
     for kwargs in (dict(W=0), dict(W=257), dict(reduce_order=2), dict(unroll=3), dict(nontemporal=2), dict(lane_elems=3),
-                   dict(lane_elems=2, unroll=4), dict(resident_workgroups=2), dict(resident_workgroups=9)):
+                   dict(lane_elems=2, unroll=4), dict(resident_workgroups=2), dict(resident_workgroups=9),
+                   dict(autotune=True, unroll=2)):
         args = dict(W=2, lr=0.1)
         args.update(kwargs)
         with pytest.raises(kv.KVError) as e:
