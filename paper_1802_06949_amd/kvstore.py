@@ -238,7 +238,13 @@ class PushList:
 
 
 class KVStore:
-    """kv_init ... kv_destroy."""
+    """kv_init ... kv_destroy: one store for a fixed key set (argument marshalling only; see include/kv.h).
+
+    key_numel[k] is the element count of key k; W gradient copies per key of dtype grad_dtype ("f32" / "f16");
+    keys smaller than bucket_bytes (one copy) are packed into buckets.  keep_sum / descending / lazy / autotune are
+    the kv_flags; stream is a hipStream_t address (default: torch's current stream); the remaining keyword
+    arguments are the kv_tuning fields (0 or -1 = the library's default).
+    """
 
     def __init__(self, key_numel: Sequence[int], W: int, grad_dtype="f32", bucket_bytes: int = 1 << 22, *,
                  lr: float, momentum: float = 0.0, wd: float = 0.0, rescale: float = 0.0,
