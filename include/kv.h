@@ -245,6 +245,24 @@ int kv_push_list(kv_store* store, int nkeys, const int* keys /* host */, const v
  * log and the launch counter count a captured launch once, when it is recorded.
  */
 int kv_release_captures(kv_store* store);
+/*
+ * kv_push_list_noalloc: kv_push_list for callers that cannot allocate or upload: code under HIP graph
+ * capture that pushes buffers the store has not seen before, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same values, same launch order.  The call allocates nothing on the host or
+ * the device and copies nothing from host memory: the gradient-pointer table its launches read is a
+ * file-scope device array that the library's code object carries (512 KiB on every GPU the library
+ * runs on, held until the process ends), filled by a small kernel that takes the pointers in its
+ * arguments (one fill launch per 384 pointers before each fused launch).
+ *   - Limit: num_keys * W <= 65536 pointers; a larger store gets KV_ERR_ARG and nothing happens.
+ *   - Chained schedule only (KV_ERR_STATE otherwise).
+ *   - Every store on a GPU shares that GPU's array, which keeps the rows of the last call.  Calls on one
+ *     stream are ordered by the stream.  Calls whose launches can overlap on one GPU (stores on different
+ *     streams, or graph replays racing with eager calls on another stream) race on the rows they share:
+ *     the caller must order them.
+ *   - May be called while the stream is captured; the capture needs no earlier push of the same buffers
+ *     and pins no table.  A replay rewrites the rows it needs before it reads them.
+ */
+int kv_push_list_noalloc(kv_store* store, int nkeys, const int* keys /* host */, const void* const* dev_grads /* host */);
 /* The launch tuning in force (the defaults resolved, or what KV_FLAG_AUTOTUNE has chosen so far);
  * *tuning_done_out (may be NULL) is 0 while a store that tunes itself is still trying shapes. */
 int kv_get_tuning(const kv_store* store, kv_tuning* tuning_out /* host */, int* tuning_done_out /* host */);

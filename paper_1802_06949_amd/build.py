@@ -40,6 +40,7 @@ def _jobs():
             jobs.append((os.path.join(CSRC, "kv_fused.hip"), os.path.join(OBJ, f"kv_fused_f{f16}_w{w}.o"),
                          DEVICE + [f"-DKV_TU_F16={f16}", f"-DKV_TU_W={w}"]))
     jobs.append((os.path.join(CSRC, "kv_dispatch.hip"), os.path.join(OBJ, "kv_dispatch.o"), DEVICE))
+    jobs.append((os.path.join(CSRC, "kv_static.hip"), os.path.join(OBJ, "kv_static.o"), DEVICE))
     jobs.append((os.path.join(CSRC, "kv_plan.cpp"), os.path.join(OBJ, "kv_plan.o"), []))
     jobs.append((os.path.join(CSRC, "kv_store.cpp"), os.path.join(OBJ, "kv_store.o"), []))
     jobs.append((os.path.join(CSRC, "kv_engine.cpp"), os.path.join(OBJ, "kv_engine.o"), []))

@@ -42,3 +42,12 @@ hipError_t kv_launch_mix(void* const* bufs, int n_read, int n_write, size_t byte
 // that key), replicas are fp32 or, with rep_f16, fp16 rounded to nearest even.
 hipError_t kv_launch_replicate(const KvTile* tiles, int64_t tile_lo, int64_t tile_hi, const float* arena,
                                const void* const* rows, int n_rep, int rep_f16, hipStream_t stream);
+
+// Allocation-free pointer table: one file-scope device array per GPU of KV_STATIC_TABLE_PTRS gradient
+// pointers (512 KiB), filled by a kernel that carries up to KV_FILL_PTRS pointers per launch in its arguments.
+constexpr int KV_STATIC_TABLE_PTRS = 65536;
+constexpr int KV_FILL_PTRS = 384;
+// Device address of that array on `device`, which must be the current device (looked up once per device).
+hipError_t kv_static_table(int device, const void*** table_out);
+// table[first + i] = host_ptrs[i] for i < n, on `stream`; no allocation and no host-to-device copy.
+hipError_t kv_launch_fill_rows(const void** table, size_t first, const void* const* host_ptrs, size_t n, hipStream_t stream);

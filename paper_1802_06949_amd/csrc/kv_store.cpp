@@ -102,6 +102,9 @@ struct kv_store {
     int last_slot = 0;
     int next_victim = 0;
 
+    const void** static_table = nullptr;          // this GPU's file-scope pointer table (kv_push_list_noalloc)
+    bool static_call = false;                     // launches of the current call read that table
+
     const void** h_stage = nullptr;               // pinned, NSTAGE * table_elems
     hipEvent_t stage_ev[NSTAGE] = {};
     bool stage_busy[NSTAGE] = {};
@@ -193,6 +196,12 @@ int check_key(kv_store* st, int key) {
 int table_for(kv_store* st, int s0, int s1, hipStream_t stream, const void* const** table_out) {
     const size_t W = (size_t)st->W;
     const size_t lo = (size_t)s0 * W, n = (size_t)(s1 - s0) * W;
+    if (st->static_call) {
+        // the rows go into the file-scope table by kernel, in stream order before the launch that reads them
+        KV_HIP(st, kv_launch_fill_rows(st->static_table, lo, &st->cur_ptrs[lo], n, stream));
+        *table_out = st->static_table;
+        return KV_OK;
+    }
     // A launch that is being captured may only read one of the tables its pushes were checked
     // against, preferably one that an earlier capture already holds; the table is then held too.
     for (int pass = st->capture_launch ? 0 : 1; pass < 2; ++pass) {
@@ -807,6 +816,7 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     } while (0)
 
     KV_INIT_HIP(hipGetDevice(&st->device));
+    KV_INIT_HIP(kv_static_table(st->device, &st->static_table));
     int cus = 0;
     KV_INIT_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, st->device));
     if (cus > 0) st->num_cus = cus;
@@ -958,11 +968,25 @@ int kv_push(kv_store* store, int key, const void* const* dev_grads) {
     return rc;
 }
 
-int kv_push_list(kv_store* store, int nkeys, const int* keys, const void* const* dev_grads) {
+// Both list pushes.  With static_table the launches read this GPU's file-scope pointer table, filled by
+// kernel: nothing is uploaded, so a capture needs no table from an earlier push.
+static int push_list_common(kv_store* store, int nkeys, const int* keys, const void* const* dev_grads, bool static_table,
+                            const char* fn) {
     if (!store) return KV_ERR_ARG;
     if (nkeys < 0 || (nkeys > 0 && (!keys || !dev_grads))) {
-        set_err(store->err, "kv_push_list: bad arguments");
+        set_err(store->err, "%s: bad arguments", fn);
         return KV_ERR_ARG;
+    }
+    if (static_table) {
+        if (store->schedule != KV_SCHED_CHAINED) {
+            set_err(store->err, "%s: chained schedule only", fn);
+            return KV_ERR_STATE;
+        }
+        if (store->table_elems > (size_t)KV_STATIC_TABLE_PTRS) {
+            set_err(store->err, "%s: %zu keys x %d gradient copies = %zu pointers, more than the %d the static table holds",
+                    fn, store->plan.seg_key.size(), store->W, store->table_elems, KV_STATIC_TABLE_PTRS);
+            return KV_ERR_ARG;
+        }
     }
     const bool captured = capturing(store);
     if (captured && store->schedule != KV_SCHED_CHAINED) return capture_check(store, 0, nullptr, nullptr);
@@ -986,10 +1010,19 @@ int kv_push_list(kv_store* store, int nkeys, const int* keys, const void* const*
             return KV_ERR_STATE;
         }
     }
-    if (captured) {
+    const bool fresh = store->chain.pending_keys == 0 && store->chain.next_unit == 0;
+    if (captured && static_table) {
+        if (!fresh && !store->capture_iteration) {
+            set_err(store->err, "%s while the stream is being captured, but the iteration began before the capture: "
+                                "a capture holds whole iterations", fn);
+            return KV_ERR_STATE;
+        }
+        if (fresh) store->capture_mask = 0;            // no cached table is known to hold this iteration
+        store->capture_iteration = true;
+    } else if (captured) {
         int rc = capture_check(store, nkeys, keys, dev_grads);
         if (rc != KV_OK) return rc;
-    } else if (store->chain.pending_keys == 0 && store->chain.next_unit == 0) {
+    } else if (fresh) {
         store->capture_iteration = false;
     }
     for (int i = 0; i < nkeys; ++i) {
@@ -1005,9 +1038,19 @@ int kv_push_list(kv_store* store, int nkeys, const int* keys, const void* const*
     }
     for (int i = 0; i < nkeys; ++i) record_grads(store, keys[i], dev_grads + (size_t)i * store->W);
     store->capture_launch = captured;
+    store->static_call = static_table;
     const int rc = drain_chain(store);
+    store->static_call = false;
     store->capture_launch = false;
     return rc;
+}
+
+int kv_push_list(kv_store* store, int nkeys, const int* keys, const void* const* dev_grads) {
+    return push_list_common(store, nkeys, keys, dev_grads, false, "kv_push_list");
+}
+
+int kv_push_list_noalloc(kv_store* store, int nkeys, const int* keys, const void* const* dev_grads) {
+    return push_list_common(store, nkeys, keys, dev_grads, true, "kv_push_list_noalloc");
 }
 
 int kv_pull(kv_store* store, int key, void* dev_out_f32) { return pull_common(store, key, dev_out_f32, 0); }

@@ -84,6 +84,7 @@ def load_library() -> ctypes.CDLL:
     sig("kv_get_sgd_params", c_int, c_vp, P(_SgdParams))
     sig("kv_push", c_int, c_vp, c_int, P(c_vp))
     sig("kv_push_list", c_int, c_vp, c_int, P(c_int), P(c_vp))
+    sig("kv_push_list_noalloc", c_int, c_vp, c_int, P(c_int), P(c_vp))
     sig("kv_pull", c_int, c_vp, c_int, c_vp)
     sig("kv_pull_list", c_int, c_vp, c_int, P(c_int), P(c_vp))
     sig("kv_pull_grad", c_int, c_vp, c_int, c_vp)
@@ -327,6 +328,10 @@ class KVStore:
 
     def push_list(self, pl: PushList) -> None:
         self._check(self._L.kv_push_list(self._h, pl.n, pl.keys, pl.ptrs))
+
+    def push_list_noalloc(self, pl: PushList) -> None:
+        """kv_push_list_noalloc: the list push that allocates and uploads nothing (static device pointer table)."""
+        self._check(self._L.kv_push_list_noalloc(self._h, pl.n, pl.keys, pl.ptrs))
 
     def get_tuning(self) -> Tuple[dict, bool]:
         """kv_get_tuning: the launch tuning in force and whether a self-tuning store has settled."""
