@@ -32,13 +32,18 @@ METRIC = "aggregated gradient bytes/s (GB/s, % HBM peak) for W-way reduce+SGD up
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=6000)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..5 (3 = ResNet-50-shaped, W=8)")
     ap.add_argument("--ranks", type=int, default=0, help="override the configuration's W (characterisation runs)")
     ap.add_argument("--grad-dtype", choices=["f32", "f16"], default=None, help="override the gradient dtype")
     ap.add_argument("--sets", type=int, default=2, help="distinct gradient sets cycled through (fresh buffers each step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cold-steps", type=int, default=40,
+                    help="steps of the cold-state legs: before each one a plain pass over 1 GiB of unrelated memory "
+                         "flushes L2 and the memory-side cache, outside the step's event pair (0 = skip)")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the legs on the other benchmark configurations (1, 2, 4, 5 and 6)")
     ap.add_argument("--cpu-seconds", type=float, default=8.0,
                     help="CPU work per oracle leg (single thread, all cores); whole steps are run until it is used up")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="N",
@@ -84,13 +89,18 @@ def parse_args():
 
 
 def read_traffic(workload: str):
-    """HBM bytes per launch from the committed counter summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    """HBM bytes per launch from the committed counter summary of this workload, and where it comes from."""
+    name = f"hbm_traffic_{workload}.txt"
+    path = os.path.join(ROOT, "profiles", name)
     if not os.path.exists(path):
-        return None
-    vals = {}
+        return None, None
+    vals, meta = {}, {"file": f"profiles/{name}"}
     with open(path) as f:
         for line in f:
+            body = line.lstrip("# ").strip()
+            for tag in ("measured_at_commit", "measured_on"):
+                if body.startswith(tag + ":"):
+                    meta[tag] = body.split(":", 1)[1].strip()
             if ":" in line and not line.lstrip().startswith("#"):
                 k, v = line.split(":", 1)
                 try:
@@ -98,8 +108,153 @@ def read_traffic(workload: str):
                 except (ValueError, IndexError):
                     pass
     if "fetch_bytes_per_launch" in vals and "write_bytes_per_launch" in vals:
-        return vals["fetch_bytes_per_launch"] + vals["write_bytes_per_launch"]
-    return None
+        meta["note"] = "rocprofv3 FETCH_SIZE / WRITE_SIZE between L2 and the fabric, from that earlier run, not from this one"
+        return vals["fetch_bytes_per_launch"] + vals["write_bytes_per_launch"], meta
+    return None, None
+
+
+MALL_BYTES = 256 << 20          # memory-side cache of the MI355X
+EVICT_BYTES = 1 << 30
+
+
+def device_gradients(cfg, nsets: int, seed: int):
+    """Seeded gradients drawn on the GPU (timing legs of the other configurations: values do not change the time of a
+    bandwidth-bound kernel, and 2.2e9 host draws for the VGG-16 shape would take longer than every timed leg)."""
+    import torch
+    import workloads as wl
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    sigma, zeros = wl.key_sigma(cfg), wl.zero_keys(cfg)
+    tdt = torch.float32 if cfg.grad_dtype == "f32" else torch.float16
+    sets = []
+    for _ in range(nsets):
+        one = []
+        for k, n in enumerate(cfg.numel):
+            if k in zeros:
+                one.append([torch.zeros(n, dtype=tdt, device="cuda") for _ in range(cfg.W)])
+            else:
+                one.append([(torch.randn(n, device="cuda", generator=gen) * float(sigma[k])).to(tdt) for _ in range(cfg.W)])
+        sets.append(one)
+    return sets
+
+
+def launch_floor_us(kv, reps: int = 2000) -> float:
+    """Average time per launch of an empty kernel, back to back on the current stream."""
+    import torch
+    kv.null_launch(50)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    kv.null_launch(reps)                 # one native loop: no interpreter between the launches
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps
+
+
+def cold_leg(kv, store, do_step, steps: int, evict_buf, dirty: bool, alg_bytes_step: float):
+    """Steps that find nothing of theirs in L2 or the memory-side cache: a plain pass over 1 GiB of unrelated memory
+    runs before each step, outside the step's pair of events (all on the store's stream)."""
+    if steps <= 0:
+        return None
+    for i in range(2):
+        kv.evict_caches(evict_buf, EVICT_BYTES, dirty)
+        do_step(i)
+    store.wait()
+    before = store.launch_log(0)[0]
+    store.timing_begin()
+    for i in range(steps):
+        kv.evict_caches(evict_buf, EVICT_BYTES, dirty)
+        store.timing_mark()
+        do_step(i)
+        store.timing_mark()
+    store.wait()
+    store.timing_end()
+    launches = store.launch_log(0)[0] - before
+    iv = store.timing_intervals()[1::2]
+    total_s = sum(iv) * 1e-3
+    lps = launches / steps
+    launch_s = total_s / max(launches, 1)
+    achieved = alg_bytes_step / max(lps, 1e-9) / launch_s / 1e9
+    srt = sorted(iv)
+    return {
+        "evict": "1 GiB plain read-modify-write pass before every step: caches full of modified unrelated lines, which the "
+                 "step's own allocations force back to memory (worst case)" if dirty else
+                 "1 GiB plain read pass before every step: caches full of clean unrelated lines; w' and m' may end the "
+                 "step in the memory-side cache and be written back later",
+        "achieved": round(achieved, 2),
+        "frac": round(achieved / HBM_PEAK_GBPS, 4),
+        "avg_launch_us": round(launch_s * 1e6, 3),
+        "median_step_us": round(srt[len(srt) // 2] * 1e3, 3),
+        "steps": steps,
+    }
+
+
+def other_config_leg(kv, cfg_id: int, evict_buf, cold_steps: int, floor_us: float):
+    """One of the other benchmark configurations, in this process, same event method as the headline."""
+    import torch
+    import workloads as wl
+    cfg = wl.get_config(cfg_id)
+    K, N = len(cfg.keys), cfg.total_numel
+    nsets = 1 if cfg.algorithmic_bytes_per_step > (4 << 30) else 2
+    dev_sets = device_gradients(cfg, nsets, 1000 + cfg_id)
+    store = kv.KVStore(cfg.numel, cfg.W, cfg.grad_dtype, cfg.bucket_bytes, lr=cfg.lr, momentum=cfg.momentum, wd=cfg.wd)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(2000 + cfg_id)
+    for k, n in enumerate(cfg.numel):
+        if n:
+            store.set_weights(k, torch.randn(n, device="cuda", generator=gen) * 0.05)
+    lists = [store.make_push_list(list(range(K)), d) for d in dev_sets]
+
+    def do_step(i):
+        store.push_list(lists[i % nsets])
+
+    alg = cfg.algorithmic_bytes_per_step
+    steps = int(max(30, min(20000, 0.4 / max(alg / 6.0e12, 4e-6))))      # about 0.4 s of launches
+    for i in range(10):
+        do_step(i)
+    store.wait()
+    store.timing_begin()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        do_step(i)
+    store.wait()
+    wall = time.perf_counter() - t0
+    ev_ms, launches = store.timing_end()
+    lps = launches / steps
+    launch_s = ev_ms * 1e-3 / max(launches, 1)
+    state_bytes = 16 * N
+    out = {
+        "workload": f"{cfg.name}: {K} keys, {N} params, W={cfg.W} {cfg.grad_dtype}, bucket {cfg.bucket_bytes} B",
+        "data": f"gradients N(0, sigma_key) drawn on the GPU, {nsets} set(s) cycled",
+        "steps": steps,
+        "ms_per_step": round(wall / steps * 1e3, 5),
+        "avg_launch_us": round(launch_s * 1e6, 3),
+        "launches_per_step": lps,
+        "units": store.plan.num_units,
+        "value_GBps": round(N * cfg.W * cfg.grad_itemsize / (wall / steps) / 1e9, 2),
+        "algorithmic_bytes_per_step": alg,
+        "algorithmic_frac": round(alg / max(lps, 1e-9) / launch_s / 1e9 / HBM_PEAK_GBPS, 4),
+        "tuning": store.get_tuning()[0],
+    }
+    if alg < (64 << 20):
+        out["note"] = (f"launch bound and cache resident ({alg / 1e6:.1f} MB per step): the fraction says little; an empty "
+                       f"kernel launch takes {floor_us:.2f} us on this box")
+        out["launch_floor_us"] = round(floor_us, 3)
+    if state_bytes // 2 > MALL_BYTES:
+        out["cold_frac"] = out["algorithmic_frac"]
+        out["cold_note"] = "w and m (%.0f MB) cannot stay in the 256 MiB memory-side cache: every step is a cold step" % (state_bytes / 2e6)
+    else:
+        cold = cold_leg(kv, store, do_step, cold_steps, evict_buf, False, alg)
+        cold_d = cold_leg(kv, store, do_step, cold_steps, evict_buf, True, alg)
+        if cold:
+            out["cold_frac"] = cold["frac"]
+            out["cold_avg_launch_us"] = cold["avg_launch_us"]
+            out["cold_dirty_frac"] = cold_d["frac"]
+            out["cold_dirty_avg_launch_us"] = cold_d["avg_launch_us"]
+    store.close()
+    del dev_sets, lists
+    torch.cuda.empty_cache()
+    return out
 
 
 def cpu_baseline(cfg, weights, grads_host, seconds: float):
@@ -406,6 +561,20 @@ def main() -> int:
         torch.cuda.synchronize()
         extra["calib_copy_bytes"] = nb
 
+    # cold-state legs of the headline workload, then the other configurations, all in this process
+    traffic, traffic_source = read_traffic(cfg.name)
+    cold = cold_dirty = None
+    evict_buf = None
+    plain = args.schedule == "chained" and not args.graph and args.broadcast == "none"
+    if plain and (args.cold_steps > 0 or not args.no_other_configs):
+        evict_buf = torch.zeros(EVICT_BYTES // 4, dtype=torch.float32, device="cuda")
+    if plain and args.cold_steps > 0:
+        cold = cold_leg(kv, store, do_step, args.cold_steps, evict_buf, False, alg_bytes_step)
+        cold_dirty = cold_leg(kv, store, do_step, args.cold_steps, evict_buf, True, alg_bytes_step)
+    floor_us = launch_floor_us(kv)
+    state_bytes = 8 * N
+    grad_bytes = N * cfg.W * itemsize
+
     result = {
         "metric": METRIC,
         "value": round(agg_gbps, 2),
@@ -442,15 +611,34 @@ def main() -> int:
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": read_traffic(cfg.name),
+            "traffic": traffic,
+            "traffic_source": traffic_source,
             "algorithmic_bytes_per_launch": alg_bytes_launch,
             "avg_launch_us": round(launch_s * 1e6, 3),
             "median_step_us_with_event_per_step": round(step_ms[len(step_ms) // 2] * 1e3, 3) if step_ms else None,
             "min_step_us_with_event_per_step": round(step_ms[0] * 1e3, 3) if step_ms else None,
             "launches_timed": launches,
+            "state_residency": (
+                f"steps run back to back: the {state_bytes / 1e6:.0f} MB of w and m fit the 256 MiB memory-side cache and stay "
+                f"there between launches, so {2 * state_bytes / alg_bytes_step:.0%} of the algorithmic bytes (w, m read and "
+                f"written) never reach DRAM; DRAM itself delivers the {grad_bytes / 1e6:.0f} MB of gradients per launch "
+                f"({grad_bytes / launch_s / 1e9:.0f} GB/s, {grad_bytes / launch_s / 1e9 / HBM_PEAK_GBPS:.0%} of peak); "
+                "roofline.cold has the same launch with the state evicted" if state_bytes <= MALL_BYTES else
+                f"the {state_bytes / 1e6:.0f} MB of w and m do not fit the 256 MiB memory-side cache: every launch reads "
+                "and writes them in DRAM"),
+            "cold": cold,
+            "cold_dirty": cold_dirty,
         },
+        "launch_floor_us": round(floor_us, 3),
     }
     result.update(extra)
+    if plain and not args.no_other_configs:
+        others = []
+        for cid in (1, 2, 4, 5, 6):
+            if cid != args.config:
+                others.append(other_config_leg(kv, cid, evict_buf, args.cold_steps, floor_us))
+        result["other_configs"] = others
+    del evict_buf
 
     if not args.no_cpu_baseline:
         base = cpu_baseline(cfg, weights, host_sets[0], args.cpu_seconds)
@@ -461,7 +649,9 @@ def main() -> int:
             "cores": threads,
             "kind": "oracle",
             "sample": f"{cpu_steps} full steps of the same workload (all {K} keys, one gradient set), after one "
-                      f"untimed step; the single-thread leg ran {base['single'][2]} steps",
+                      f"untimed step; the single-thread leg ran {base['single'][2]} steps.  The all-core leg is the "
+                      "unmodified oracle: it cuts each key into one element range per core with a thread pool made per "
+                      "key, and runs keys below 4096 elements per core on one thread, so it does not scale with the cores",
             "ms_per_step": round(dt * 1e3, 2),
             "single_thread_value": round(N * cfg.W * itemsize / base["single"][1] / 1e9, 3),
             "single_thread_ms_per_step": round(base["single"][1] * 1e3, 2),

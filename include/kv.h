@@ -207,7 +207,9 @@ void kv_destroy(kv_store* store);                              /* drains the str
  * pushes and pulls of the key; src may be reused as soon as that stream's order allows. */
 int kv_set_weights (kv_store* store, int key, const void* src_f32);
 int kv_set_momentum(kv_store* store, int key, const void* src_f32);
-int kv_set_lr(kv_store* store, float lr);                      /* takes effect at the next launch */
+/* Learning rate from the next launch on.  The paper's Evaluation section starts from 0.1 and grows the rate with
+ * the mini-batch, i.e. with the number of GPUs, up to 1.0 at 256 GPUs; a schedule is a sequence of these calls. */
+int kv_set_lr(kv_store* store, float lr);
 /* All optimizer parameters at once (same rules as at kv_init; they take effect at the next launch),
  * and the ones in force; params_out->rescale is the resolved factor (1/W if it was given as <= 0). */
 int kv_set_sgd_params(kv_store* store, const kv_sgd_params* params /* host */);
@@ -349,21 +351,6 @@ int kv_timing_end(kv_store* store, float* ms_out, int64_t* launches_out);
  * at most cap values) and returns how many it wrote: per-step times without a host wait per step. */
 int kv_timing_mark(kv_store* store);
 int kv_timing_intervals(kv_store* store, float* ms_out, int cap);
-/* Plain streaming copy kernel (float4 grid-stride) of `bytes` bytes (multiple of 16,
- * both pointers 16-byte aligned) on hip_stream: the known-size kernel against which
- * hardware byte counters are calibrated. */
-int kv_copy_bytes(void* dev_dst, const void* dev_src, size_t bytes, void* hip_stream);
-/* Plain streaming read kernel: reads `bytes` bytes (multiple of 16, pointer 16-byte aligned) and
- * writes nothing.  With kv_copy_bytes it gives the measured read and copy ceilings of the GPU that the
- * fused kernel's rate is put next to. */
-int kv_read_bytes(const void* dev_src, size_t bytes, void* hip_stream);
-/* Measured ceiling for a MIX of streams with 16 bytes per lane and stream (one workgroup per 4 KB
- * of every stream, all loads in flight before the first store): every lane sums its 16-byte
- * vector of n_read buffers (1, 2, 4, 8, 16 or 32) and stores the sum to each of n_write buffers
- * (0..8).  dev_bufs: host array of n_read + n_write device pointers, read buffers first, each to
- * `bytes` bytes (multiple of 16), 16-byte aligned, none overlapping a written one.  KV_ERR_ARG otherwise. */
-int kv_stream_mix(void* const* dev_bufs /* host */, int n_read, int n_write, size_t bytes, void* hip_stream);
-
 /* Message for the last failure on this store (or, with NULL, of the last failed
  * kv_init / kv_plan_create / kv_chain_create on this thread).  Never NULL. */
 const char* kv_last_error(const kv_store* store);

@@ -43,6 +43,7 @@ def _jobs():
     jobs.append((os.path.join(CSRC, "kv_static.hip"), os.path.join(OBJ, "kv_static.o"), DEVICE))
     jobs.append((os.path.join(CSRC, "kv_plan.cpp"), os.path.join(OBJ, "kv_plan.o"), []))
     jobs.append((os.path.join(CSRC, "kv_store.cpp"), os.path.join(OBJ, "kv_store.o"), []))
+    jobs.append((os.path.join(CSRC, "kv_diag.cpp"), os.path.join(OBJ, "kv_diag.o"), []))
     jobs.append((os.path.join(CSRC, "kv_engine.cpp"), os.path.join(OBJ, "kv_engine.o"), []))
     return jobs
 

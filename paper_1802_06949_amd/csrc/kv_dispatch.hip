@@ -34,6 +34,25 @@ __global__ void __launch_bounds__(KV_THREADS) kv_read_kernel(const f32x4* __rest
     if (acc.x == -12345.678f && acc.y == 3.25f) sink[0] = acc;
 }
 
+// Plain cached loads and stores: every line of the buffer passes through L2 and the memory-side cache.
+template <bool DIRTY>
+__global__ void __launch_bounds__(KV_THREADS) kv_touch_kernel(f32x4* __restrict__ buf, size_t nvec) {
+    const size_t stride = (size_t)gridDim.x * KV_THREADS;
+    f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (size_t i = (size_t)blockIdx.x * KV_THREADS + threadIdx.x; i < nvec; i += stride) {
+        f32x4 v = buf[i];
+        if constexpr (DIRTY) {
+            v.x += 1.0f;
+            buf[i] = v;
+        } else {
+            acc += v;
+        }
+    }
+    // the sum can never equal the sentinel, but the compiler cannot know that, so the loads stay
+    if (!DIRTY && acc.x == -12345.678f && acc.y == 3.25f) buf[0] = acc;
+}
+__global__ void kv_null_kernel() {}
+
 // R read streams and n_write written streams with the access pattern of the fused kernel: one
 // workgroup per 4 KB tile of every stream, every load in flight before the first store.
 struct KvMixArgs {
@@ -198,5 +217,20 @@ hipError_t kv_launch_mix(void* const* bufs, int n_read, int n_write, size_t byte
         default: return hipErrorInvalidValue;
     }
 #undef KV_MIX
+    return hipGetLastError();
+}
+
+hipError_t kv_launch_touch(void* buf, size_t bytes, bool dirty, hipStream_t stream) {
+    const size_t nvec = bytes / 16;
+    if (nvec == 0) return hipSuccess;
+    size_t blocks = (nvec + KV_THREADS - 1) / KV_THREADS;
+    if (blocks > (1u << 22)) blocks = 1u << 22;
+    if (dirty) hipLaunchKernelGGL(kv_touch_kernel<true>, dim3((unsigned)blocks), dim3(KV_THREADS), 0, stream, static_cast<f32x4*>(buf), nvec);
+    else hipLaunchKernelGGL(kv_touch_kernel<false>, dim3((unsigned)blocks), dim3(KV_THREADS), 0, stream, static_cast<f32x4*>(buf), nvec);
+    return hipGetLastError();
+}
+
+hipError_t kv_launch_null(hipStream_t stream) {
+    hipLaunchKernelGGL(kv_null_kernel, dim3(1), dim3(64), 0, stream);
     return hipGetLastError();
 }

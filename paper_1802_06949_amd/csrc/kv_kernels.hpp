@@ -51,3 +51,9 @@ constexpr int KV_FILL_PTRS = 384;
 hipError_t kv_static_table(int device, const void*** table_out);
 // table[first + i] = host_ptrs[i] for i < n, on `stream`; no allocation and no host-to-device copy.
 hipError_t kv_launch_fill_rows(const void** table, size_t first, const void* const* host_ptrs, size_t n, hipStream_t stream);
+
+// Plain cached pass over `bytes` bytes (multiple of 16), loads only or (dirty) read-modify-write: leaves this
+// buffer's lines, and nothing else, in the caches it is larger than.
+hipError_t kv_launch_touch(void* buf, size_t bytes, bool dirty, hipStream_t stream);
+// One empty workgroup.
+hipError_t kv_launch_null(hipStream_t stream);

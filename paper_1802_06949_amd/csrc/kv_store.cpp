@@ -19,6 +19,7 @@
 #include <vector>
 
 #include "../../include/kv.h"
+#include "kv_error.hpp"
 #include "kv_kernels.hpp"
 #include "kv_plan.hpp"
 
@@ -34,6 +35,12 @@ void set_err(std::string& dst, const char* fmt, ...) {
     va_end(ap);
     dst = buf;
 }
+
+}  // namespace
+
+void kv_set_global_error(const char* message) { g_err = message ? message : ""; }
+
+namespace {
 
 constexpr int NSLOT = 8;    // cached device pointer tables
 constexpr int NSTAGE = 8;   // pinned staging chunks in flight
@@ -1395,52 +1402,6 @@ int kv_timing_end(kv_store* store, float* ms_out, int64_t* launches_out) {
     KV_HIP(store, hipEventElapsedTime(ms_out, store->t0, store->t1));
     if (launches_out) *launches_out = store->launches_total - store->launches_at_begin;
     store->timing_active = false;
-    return KV_OK;
-}
-
-int kv_copy_bytes(void* dev_dst, const void* dev_src, size_t bytes, void* hip_stream) {
-    if (!dev_dst || !dev_src || (bytes & 15u) || ((uintptr_t)dev_dst & 15u) || ((uintptr_t)dev_src & 15u)) {
-        set_err(g_err, "kv_copy_bytes: pointers and size must be multiples of 16");
-        return KV_ERR_ARG;
-    }
-    hipError_t e = kv_launch_copy(dev_dst, dev_src, bytes, static_cast<hipStream_t>(hip_stream));
-    if (e != hipSuccess) {
-        set_err(g_err, "kv_copy_bytes: %s", hipGetErrorString(e));
-        return KV_ERR_HIP;
-    }
-    return KV_OK;
-}
-
-int kv_read_bytes(const void* dev_src, size_t bytes, void* hip_stream) {
-    if (!dev_src || (bytes & 15u) || ((uintptr_t)dev_src & 15u)) {
-        set_err(g_err, "kv_read_bytes: pointer and size must be multiples of 16");
-        return KV_ERR_ARG;
-    }
-    hipError_t e = kv_launch_read(dev_src, bytes, static_cast<hipStream_t>(hip_stream));
-    if (e != hipSuccess) {
-        set_err(g_err, "kv_read_bytes: %s", hipGetErrorString(e));
-        return KV_ERR_HIP;
-    }
-    return KV_OK;
-}
-
-int kv_stream_mix(void* const* dev_bufs, int n_read, int n_write, size_t bytes, void* hip_stream) {
-    const bool r_ok = n_read == 1 || n_read == 2 || n_read == 4 || n_read == 8 || n_read == 16 || n_read == 32;
-    if (!dev_bufs || !r_ok || n_write < 0 || n_write > 8 || (bytes & 15u)) {
-        set_err(g_err, "kv_stream_mix: n_read must be 1, 2, 4, 8, 16 or 32, n_write 0..8, bytes a multiple of 16");
-        return KV_ERR_ARG;
-    }
-    for (int s = 0; s < n_read + n_write; ++s) {
-        if (!dev_bufs[s] || ((uintptr_t)dev_bufs[s] & 15u)) {
-            set_err(g_err, "kv_stream_mix: buffer %d is null or not aligned to 16 bytes", s);
-            return KV_ERR_ARG;
-        }
-    }
-    hipError_t e = kv_launch_mix(dev_bufs, n_read, n_write, bytes, static_cast<hipStream_t>(hip_stream));
-    if (e != hipSuccess) {
-        set_err(g_err, "kv_stream_mix: %s", hipGetErrorString(e));
-        return KV_ERR_HIP;
-    }
     return KV_OK;
 }
 

@@ -106,6 +106,8 @@ def load_library() -> ctypes.CDLL:
     sig("kv_copy_bytes", c_int, c_vp, c_vp, c_sz, c_vp)
     sig("kv_read_bytes", c_int, c_vp, c_sz, c_vp)
     sig("kv_stream_mix", c_int, P(c_vp), c_int, c_int, c_sz, c_vp)
+    sig("kv_evict_caches", c_int, c_vp, c_sz, c_int, c_vp)
+    sig("kv_null_launch", c_int, c_int, c_vp)
     sig("kv_last_error", ctypes.c_char_p, c_vp)
     _lib = L
     return L
@@ -453,5 +455,28 @@ def stream_mix(read_bufs: Sequence, write_bufs: Sequence, nbytes: int, stream: O
     bufs = list(read_bufs) + list(write_bufs)
     arr = (ctypes.c_void_p * max(len(bufs), 1))(*[int(b.data_ptr()) for b in bufs])
     rc = L.kv_stream_mix(arr, len(read_bufs), len(write_bufs), int(nbytes), ctypes.c_void_p(int(stream)))
+    if rc != 0:
+        raise KVError(rc, _global_error(L))
+
+
+def evict_caches(buf, nbytes: int, dirty: bool = False, stream: Optional[int] = None) -> None:
+    """kv_evict_caches: plain cached pass over a scratch buffer (cold-state timing); buf is a tensor or an address."""
+    L = load_library()
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    addr = int(buf) if isinstance(buf, int) else buf.data_ptr()
+    rc = L.kv_evict_caches(ctypes.c_void_p(addr), int(nbytes), 1 if dirty else 0, ctypes.c_void_p(int(stream)))
+    if rc != 0:
+        raise KVError(rc, _global_error(L))
+
+
+def null_launch(count: int = 1, stream: Optional[int] = None) -> None:
+    """kv_null_launch: `count` empty kernels back to back (the launch-latency floor)."""
+    L = load_library()
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    rc = L.kv_null_launch(int(count), ctypes.c_void_p(int(stream)))
     if rc != 0:
         raise KVError(rc, _global_error(L))

@@ -30,7 +30,7 @@ def _declared(*headers):
 
 
 def test_library_exports_every_declared_symbol():
-    names = _declared("kv.h", "kv_engine.h")
+    names = _declared("kv.h", "kv_engine.h", "kv_diag.h")
     assert len(names) >= 30
     lib = ctypes.CDLL(kv.library_path())
     for n in names:
@@ -40,7 +40,7 @@ def test_library_exports_every_declared_symbol():
 def test_binding_covers_every_declared_symbol():
     src = open(os.path.join(ROOT, "paper_1802_06949_amd", "kvstore.py")).read()
     src += open(os.path.join(ROOT, "paper_1802_06949_amd", "engine.py")).read()
-    for n in _declared("kv.h", "kv_engine.h"):
+    for n in _declared("kv.h", "kv_engine.h", "kv_diag.h"):
         assert f'"{n}"' in src or f"L.{n}" in src, f"{n} has no ctypes signature in the binding"
 
 
