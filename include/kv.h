@@ -123,18 +123,20 @@ typedef struct kv_sgd_params {
  *                     is 256 * lane_elems * unroll elements; (lane_elems, unroll) must be one of
  *                     (4,1) (4,2) (4,4) (2,1) (2,2) (1,1) (1,2) (1,4)
  *   workgroups_per_cu cap of resident workgroups per compute unit for the grid-stride
- *                     loop over tiles; 0 = one workgroup per tile
+ *                     loop over tiles, 1..64; 0 = one workgroup per tile; negative = default (0)
  *   nontemporal       cache policy: bit 0 = gradient loads carry the non-temporal hint; plus the policy
  *                     of the stores of w', m' (and s): 0 = plain, 4 = non-temporal, 8 = write through L2,
  *                     12 = write through L2 and non-temporal; one of 0, 1, 5, 9, 13; -1 = default (9 if
  *                     w and m together fit the 256 MiB memory-side cache, else 13)
- *   resident_workgroups  cap of workgroups resident per compute unit, 3..8 (8 = the hardware's own limit),
- *                     enforced by reserving LDS; 0 = default (a cap for 16 or 32 fp32 ranks, and for most rank
+ *   resident_workgroups  cap of workgroups resident per compute unit, 3..7, enforced by reserving LDS; 8 = no
+ *                     cap (the hardware's own limit for workgroups of 256 lanes); 0 = default (a cap for 16 or 32 fp32 ranks, and for most rank
  *                     counts when w and m do not fit the memory-side cache).  Unlike
  *                     workgroups_per_cu the grid still has one workgroup per tile.
  *   xcd_remap         how tiles are dealt to the 8 XCDs: 0 = one by one, round robin; 1 = eight contiguous
- *                     ranges, one per XCD; G > 1 = blocks of G consecutive tiles per XCD; -1 = default (64, or
- *                     1024 if w and m do not fit the memory-side cache)
+ *                     ranges, one per XCD (so a block of one tile cannot be asked for; 0 deals single tiles);
+ *                     G = 2..2^20 = blocks of G consecutive tiles per XCD, never more than an eighth of a launch;
+ *                     negative = default (64, or 1024 if w and m do not fit the memory-side cache)
+ * Values outside these ranges make kv_init fail with KV_ERR_ARG; kv_get_tuning returns the values in force.
  */
 typedef struct kv_tuning {
     int unroll;
@@ -282,7 +284,9 @@ int kv_pull_momentum(kv_store* store, int key, void* dev_out_f32);
 /* List form of kv_pull (the paper's pull takes lists of keys and tensors): dev_out_f32 is a host
  * array of nkeys device pointers, 4-byte aligned (16-byte alignment keeps the 128-bit path).  Keys
  * that are not waiting for a launch are gathered by one kernel per run of keys that are neighbours
- * in the arena (all keys: one launch); otherwise the list is served key by key as kv_pull would. */
+ * in the arena (all keys: one launch); otherwise, and whenever the stream is being captured into a graph
+ * (the gather's destination table is uploaded from reusable staging memory, which a replay must not
+ * read again), the list is served key by key as kv_pull would. */
 int kv_pull_list(kv_store* store, int nkeys, const int* keys /* host */, void* const* dev_out_f32 /* host */);
 /* Zero-copy pull: device address of the key's weights inside the arena (numel fp32,
  * 16-byte aligned, valid until kv_destroy; contents change with every step). */
@@ -312,9 +316,13 @@ int kv_broadcast_weights(kv_store* store, int key);
 int kv_wait_event(kv_store* store, void* hip_event);
 
 /*
- * kv_wait(key >= 0): blocks the host until the key's last launched update (and all
- * earlier work on the stream) is complete; KV_ERR_INCOMPLETE, without blocking, if
- * the key is pushed but its unit cannot be launched yet.
+ * kv_wait(key >= 0): blocks the host until the key's last launched update and every pull of the key issued
+ * after it are complete (the paper's WaitToRead on one tensor); KV_ERR_INCOMPLETE, without blocking, if the key is
+ * pushed but its unit cannot be launched yet.  The store records one event per launch (and per such pull) in a
+ * ring of 256 and waits for the key's event alone, so work queued later, or on other streams of the concurrent
+ * schedule, does not delay the return.  It waits for the key's whole stream instead when the ring has moved on,
+ * and after a launch that covered every unit of the store (one launch per iteration: no event is recorded on
+ * that path, and the stream holds nothing else of the iteration).
  * kv_wait(-1): barrier (the paper's Kvstore.barrier): drains the stream, then
  * returns KV_ERR_INCOMPLETE if an iteration is only partly pushed or launched.
  */

@@ -30,6 +30,11 @@
 #error "KV_TU_W must be defined"
 #endif
 
+// Ranks per batch of the kernel for a W known only at run time.
+#ifndef KV_RUNTIME_W_BATCH
+#define KV_RUNTIME_W_BATCH 8
+#endif
+
 namespace {
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -231,13 +236,28 @@ __device__ __forceinline__ void reduce_vec(const uint64_t KV_CONST* gp, int W, i
             }
         }
     } else {
-        for (int r0 = 0; r0 < W; r0 += 4) {
-            V g[4];
+        // W known only at run time: whole batches of RB ranks (their loads issued back to back, no
+        // per-rank test), then one guarded batch for the remaining W mod RB ranks; always in rank order.
+        constexpr int RB = KV_RUNTIME_W_BATCH;
+        int r0 = 0;
+        for (; r0 + RB <= W; r0 += RB) {
+            V g[RB];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < RB; ++j) g[j] = load_grad<NT>((const V KV_GLOBAL*)(gp[r0 + j] + (uint64_t)boff));
+#pragma unroll
+            for (int j = 0; j < RB; ++j) {
+                float t[N];
+                widen<N>(g[j], t);
+                f.push(t);
+            }
+        }
+        if (r0 < W) {
+            V g[RB];
+#pragma unroll
+            for (int j = 0; j < RB; ++j)
                 if (r0 + j < W) g[j] = load_grad<NT>((const V KV_GLOBAL*)(gp[r0 + j] + (uint64_t)boff));
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < RB; ++j) {
                 if (r0 + j < W) {
                     float t[N];
                     widen<N>(g[j], t);

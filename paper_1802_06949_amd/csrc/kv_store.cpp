@@ -5,7 +5,8 @@
 // run of consecutive ready units.  The gradient pointers reach the kernel through
 // a small device table; tables are cached so that a training loop that reuses its
 // gradient buffers (or alternates between a few sets) uploads nothing in steady
-// state.
+// state, and push, pull, wait and barrier allocate no host memory after kv_init
+// (tests/native/alloc_count.cpp counts).
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
@@ -45,6 +46,7 @@ namespace {
 constexpr int NSLOT = 8;    // cached device pointer tables
 constexpr int NSTAGE = 8;   // pinned staging chunks in flight
 constexpr int LOG_CAP = 4096;
+constexpr int DONE_RING = 256; // completion events kept for kv_wait(key)
 
 // One cut of the key set into tiles (depends on the elements per tile): the device table, the first
 // tile of every unit and of every segment (tiles of segment g: [seg_tile_begin[g], seg_tile_begin[g + 1])).
@@ -117,6 +119,14 @@ struct kv_store {
     bool stage_busy[NSTAGE] = {};
     int stage_next = 0;
 
+    // Completion events, one per launch (or copy) that kv_wait(key) may have to wait for, in a ring; a key
+    // remembers the serial number of the last one that covers it (-1: none, wait for the key's stream).
+    hipEvent_t done_ev[DONE_RING] = {};
+    int64_t done_serial[DONE_RING];
+    int64_t next_serial = 0;
+    std::vector<int64_t> key_serial;              // per key
+    std::vector<uint8_t> want;                    // kv_pull_list: segments asked for (sized at kv_init)
+
     std::vector<std::vector<Deferred>> deferred;  // per unit
     unsigned capture_mask = 0;                    // iteration being captured: tables that hold every key pushed so far
     bool capture_iteration = false;               // the iteration in progress began inside a capture
@@ -181,6 +191,8 @@ void free_store(kv_store* st) {
     if (st->h_stage) (void)hipHostFree(st->h_stage);
     for (int i = 0; i < NSTAGE; ++i)
         if (st->stage_ev[i]) (void)hipEventDestroy(st->stage_ev[i]);
+    for (int i = 0; i < DONE_RING; ++i)
+        if (st->done_ev[i]) (void)hipEventDestroy(st->done_ev[i]);
     for (hipStream_t l : st->lanes) (void)hipStreamDestroy(l);
     if (st->fork_ev) (void)hipEventDestroy(st->fork_ev);
     if (st->join_ev) (void)hipEventDestroy(st->join_ev);
@@ -259,12 +271,32 @@ int table_for(kv_store* st, int s0, int s1, hipStream_t stream, const void* cons
     return KV_OK;
 }
 
+bool capturing(kv_store* st);
+
+// Records the next completion event of the ring on `stream` and returns its serial number (never inside a
+// capture: a captured event record is no event the host could wait for).
+int record_done(kv_store* st, hipStream_t stream, int64_t* serial_out) {
+    const int64_t serial = st->next_serial++;
+    const int slot = (int)(serial % DONE_RING);
+    KV_HIP(st, hipEventRecord(st->done_ev[slot], stream));
+    st->done_serial[slot] = serial;
+    *serial_out = serial;
+    return KV_OK;
+}
+
 int issue_copy_out(kv_store* st, int key, void* dst, int what, hipStream_t stream) {
     const float* base = what == 0 ? st->w : what == 1 ? st->m : st->s;
     const int64_t n = st->plan.numel[key];
     if (n == 0) return KV_OK;
     KV_HIP(st, hipMemcpyAsync(dst, base + st->plan.key_arena_off[key], (size_t)n * sizeof(float), hipMemcpyDefault,
                               stream));
+    // kv_wait(key) covers the key's pulls: if the key is waited for through an event, the copy gets a later one
+    if (st->key_serial[(size_t)key] >= 0 && !st->capture_launch && !capturing(st)) {
+        int64_t serial = -1;
+        int rc = record_done(st, stream, &serial);
+        if (rc != KV_OK) return rc;
+        st->key_serial[(size_t)key] = serial;
+    }
     return KV_OK;
 }
 
@@ -407,6 +439,16 @@ int launch_run(kv_store* st, int first, int n) {
         KV_HIP(st, hipEventRecord(st->tuner.e1, st->stream));
         st->tuner.pending = true;
     }
+    // kv_wait(key) waits for this launch alone through an event.  A launch that covers the whole key set gets
+    // none (one event record per step is measurable on the headline path, and after such a launch waiting for
+    // the stream is the same thing); neither does a captured launch.
+    int64_t serial = -1;
+    if (n < (int)st->plan.units.size() && !st->capture_launch) {
+        rc = record_done(st, st->stream, &serial);
+        if (rc != KV_OK) return rc;
+    }
+    for (int u = first; u < first + n; ++u)
+        for (int k : st->plan.units[u].keys) st->key_serial[(size_t)k] = serial;
     for (int u = first; u < first + n; ++u) {
         for (const Deferred& d : st->deferred[u]) {
             rc = issue_copy_out(st, d.key, d.dst, d.what, st->stream);
@@ -466,10 +508,19 @@ int launch_key(kv_store* st, int key) {
     if (rc != KV_OK) return rc;
     rc = launch_tiles(st, sgm, sgm + 1, st->ts->seg_tile_begin[sgm], st->ts->seg_tile_begin[sgm + 1], stream, key, 0);
     if (rc != KV_OK) return rc;
+    st->key_serial[(size_t)key] = -1;
     if (st->schedule == KV_SCHED_FUNNEL) {
         // the issuing thread does the aggregation itself: nothing else is started before it is done
         KV_HIP(st, hipStreamSynchronize(stream));
-    } else if (st->outstanding > 0 && ++st->since_barrier >= st->outstanding) {
+        return KV_OK;
+    }
+    if (!st->capture_launch) {
+        int64_t serial = -1;
+        rc = record_done(st, stream, &serial);
+        if (rc != KV_OK) return rc;
+        st->key_serial[(size_t)key] = serial;
+    }
+    if (st->outstanding > 0 && ++st->since_barrier >= st->outstanding) {
         return barrier_all(st);
     }
     return KV_OK;
@@ -754,10 +805,11 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     // Elements per lane: the memory system is fastest when a lane has about 32 bytes of gradients
     // (all W ranks of one vector) in flight, i.e. many small workgroups rather than few large
     // ones; the table holds the measured best width for the rank counts that have a kernel of
-    // their own (ResNet-50-shaped key set); the kernel for any other W does best with 4, or 2 from 8 to 39 ranks.
+    // their own (ResNet-50-shaped key set).
     const int64_t state_bytes = 2 * st->plan.arena_numel * (int64_t)sizeof(float);
     const bool resident = state_bytes <= (256LL << 20);
-    int lane = W >= 8 && W < 40 ? 2 : 4;      // the kernel for any W (it loads four ranks at a time)
+    // the kernel for any W (it loads eight ranks at a time): measured on the ResNet-50-shaped key set at W = 3, 12, 40, 64
+    int lane = grad_dtype == KV_F16 ? (W < 24 ? 4 : 2) : (W < 8 ? 4 : W < 24 ? 2 : 1);
     {
         static const int w_built[5] = {2, 4, 8, 16, 32};
         static const int lane_f32[5] = {4, 2, 1, 1, 1};
@@ -799,9 +851,11 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     const bool shape_ok = (le == 4 && (un == 1 || un == 2 || un == 4)) || (le == 2 && (un == 1 || un == 2)) ||
                           (le == 1 && (un == 1 || un == 2 || un == 4));
     if (!shape_ok || !(nt == 0 || nt == 1 || nt == 5 || nt == 9 || nt == 13) ||
-        !(st->resident_wgs == 0 || (st->resident_wgs >= 3 && st->resident_wgs <= 8))) {
-        set_err(g_err, "kv_init: tuning (lane_elems, unroll) must be one of (4,1) (4,2) (4,4) (2,1) (2,2) (1,1) (1,2) (1,4) "
-                       "tuning.nontemporal one of 0, 1, 5, 9, 13 and tuning.resident_workgroups 0 or 3..8");
+        !(st->resident_wgs == 0 || (st->resident_wgs >= 3 && st->resident_wgs <= 8)) ||
+        st->wg_per_cu > 64 || st->xcd_remap > (1 << 20) || (tuning && tuning->resident_workgroups < 0)) {
+        set_err(g_err, "kv_init: tuning (lane_elems, unroll) must be one of (4,1) (4,2) (4,4) (2,1) (2,2) (1,1) (1,2) (1,4), "
+                       "tuning.nontemporal one of 0, 1, 5, 9, 13, tuning.resident_workgroups 0 or 3..8, "
+                       "tuning.workgroups_per_cu at most 64 and tuning.xcd_remap at most 2^20");
         delete st;
         return KV_ERR_ARG;
     }
@@ -845,6 +899,10 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
             st->row_valid[i].assign(st->plan.seg_key.size(), 0);
         }
         st->deferred.resize(st->plan.units.size());
+        for (size_t u = 0; u < st->plan.units.size(); ++u)      // room for a pull of w, m and s per key queued on a unit
+            st->deferred[u].reserve(3 * st->plan.units[u].keys.size());
+        st->key_serial.assign((size_t)num_keys, -1);
+        st->want.assign(st->plan.seg_key.size(), 0);
         st->log.reserve(LOG_CAP);          // the launch path never allocates
     } catch (const std::bad_alloc&) {
         set_err(g_err, "kv_init: out of host memory");
@@ -888,6 +946,10 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     KV_INIT_HIP(hipMalloc((void**)&st->d_gather, st->plan.seg_key.size() * sizeof(float*)));
     KV_INIT_HIP(hipHostMalloc((void**)&st->h_stage, (size_t)NSTAGE * st->table_elems * sizeof(void*), hipHostMallocDefault));
     for (int i = 0; i < NSTAGE; ++i) KV_INIT_HIP(hipEventCreateWithFlags(&st->stage_ev[i], hipEventDisableTiming));
+    for (int i = 0; i < DONE_RING; ++i) {
+        KV_INIT_HIP(hipEventCreateWithFlags(&st->done_ev[i], hipEventDisableTiming));
+        st->done_serial[i] = -1;
+    }
     KV_INIT_HIP(hipEventCreateWithFlags(&st->fork_ev, hipEventDisableTiming));
     KV_INIT_HIP(hipEventCreateWithFlags(&st->join_ev, hipEventDisableTiming));
     KV_INIT_HIP(hipEventCreate(&st->t0));
@@ -1071,13 +1133,12 @@ int kv_pull_list(kv_store* store, int nkeys, const int* keys, void* const* dev_o
         return KV_ERR_ARG;
     }
     const size_t nseg = store->plan.seg_key.size();
-    bool simple = store->schedule != KV_SCHED_CONCURRENT;
-    std::vector<uint8_t> want;
-    try {
-        want.assign(nseg, 0);
-    } catch (const std::bad_alloc&) {
-        return KV_ERR_NOMEM;
-    }
+    // The gather reads a table of destinations that is uploaded from a reusable pinned chunk: a capture would
+    // re-read that chunk at every replay, long after it holds something else.  Under capture (and in the
+    // concurrent schedule) the list is served key by key with device-to-device copies instead.
+    bool simple = store->schedule != KV_SCHED_CONCURRENT && !capturing(store);
+    std::vector<uint8_t>& want = store->want;
+    std::fill(want.begin(), want.end(), (uint8_t)0);
     for (int i = 0; i < nkeys; ++i) {
         int rc = check_key(store, keys[i]);
         if (rc != KV_OK) return rc;
@@ -1122,6 +1183,16 @@ int kv_pull_list(kv_store* store, int nkeys, const int* keys, void* const* dev_o
                                        store->d_gather, store->stream));
         a = b;
     }
+    // kv_wait(key) covers the key's pulls: keys waited for through an event get the event after the gather
+    int64_t serial = -1;
+    for (int i = 0; i < nkeys; ++i) {
+        if (store->key_serial[(size_t)keys[i]] < 0) continue;
+        if (serial < 0) {
+            int rc = record_done(store, store->stream, &serial);
+            if (rc != KV_OK) return rc;
+        }
+        store->key_serial[(size_t)keys[i]] = serial;
+    }
     return KV_OK;
 }
 
@@ -1145,6 +1216,12 @@ int kv_wait(kv_store* store, int key) {
         if (store->chain.marked[key]) {
             set_err(store->err, "kv_wait: key %d is pushed but its unit waits for other keys or lower units", key);
             return KV_ERR_INCOMPLETE;
+        }
+        // the event of the key's last launch (or of a pull issued after it) if the ring still holds it
+        const int64_t serial = store->key_serial[(size_t)key];
+        if (serial >= 0 && store->done_serial[serial % DONE_RING] == serial) {
+            KV_HIP(store, hipEventSynchronize(store->done_ev[serial % DONE_RING]));
+            return KV_OK;
         }
         KV_HIP(store, hipStreamSynchronize(key_stream(store, key)));
         return KV_OK;

@@ -64,7 +64,8 @@ class Engine:
         if rc != 0:
             raise KVError(rc, "kv_engine_create")
         self._h = h
-        self._keep: List[object] = []
+        self._keep: List[object] = []      # callbacks and arguments of operations that may not have run yet
+        self._pushed = 0
         self.op_copy = ctypes.cast(self._L.kv_op_copy, ctypes.c_void_p).value
         self.op_push = ctypes.cast(self._L.kv_op_push, ctypes.c_void_p).value
 
@@ -102,11 +103,16 @@ class Engine:
         rc = self._L.kv_engine_push(self._h, fn_ptr, arg_ptr, r, len(read), m, len(mutate))
         if rc != 0:
             raise KVError(rc, "kv_engine_push")
+        self._pushed += 1
 
     def wait_var(self, var: int) -> None:
         rc = self._L.kv_engine_wait_var(self._h, var)
         if rc != 0:
             raise KVError(rc, "kv_engine_wait_var")
+        # a loop that only ever waits for single variables must not keep every callback it ever pushed: once the
+        # engine has run everything pushed so far (counted after each operation has returned) nothing is referenced
+        if self.stats()[0] == self._pushed:
+            self._keep.clear()
 
     def wait_all(self) -> None:
         rc = self._L.kv_engine_wait_all(self._h)

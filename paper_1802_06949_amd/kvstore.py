@@ -223,18 +223,41 @@ class Chain:
         return self._L.kv_chain_next_unit(self._h)
 
 
-class PushList:
-    """Pre-marshalled arguments of kv_push_list; keeps the tensors alive."""
+_TORCH_DTYPE = {KV_F32: "torch.float32", KV_F16: "torch.float16"}
 
-    def __init__(self, W: int, keys: Sequence[int], grads: Sequence[Sequence]):
+
+def check_tensor(t, numel: int, dtype_code: int, what: str) -> None:
+    """Host-side bounds check before a pointer crosses the C ABI: the kernels read or write exactly `numel`
+    elements of the given dtype at data_ptr(), so anything else would be an out-of-bounds device access."""
+    if numel == 0:
+        return                                       # nothing of an empty key is ever read or written
+    if not getattr(t, "is_cuda", False):
+        raise ValueError(f"{what}: expected a tensor in GPU memory")
+    if str(t.dtype) != _TORCH_DTYPE[dtype_code]:
+        raise ValueError(f"{what}: dtype {t.dtype}, expected {_TORCH_DTYPE[dtype_code]}")
+    if t.numel() != numel:
+        raise ValueError(f"{what}: {t.numel()} elements, the key has {numel}")
+    if not t.is_contiguous():
+        raise ValueError(f"{what}: tensor is not contiguous")
+
+
+class PushList:
+    """Pre-marshalled arguments of kv_push_list; keeps the tensors alive.  With key_numel and grad_dtype (as
+    KVStore.make_push_list passes them) every tensor is checked against its key first."""
+
+    def __init__(self, W: int, keys: Sequence[int], grads: Sequence[Sequence], key_numel: Optional[Sequence[int]] = None,
+                 grad_dtype: int = KV_F32):
         if len(keys) != len(grads):
             raise ValueError("one gradient list per key expected")
         self.n = len(keys)
         self.keys = (ctypes.c_int * max(self.n, 1))(*[int(k) for k in keys])
         flat = []
-        for g in grads:
+        for key, g in zip(keys, grads):
             if len(g) != W:
                 raise ValueError(f"expected {W} gradient copies per key")
+            if key_numel is not None and 0 <= int(key) < len(key_numel):      # an unknown key is the library's to refuse
+                for r, t in enumerate(g):
+                    check_tensor(t, key_numel[int(key)], grad_dtype, f"gradient copy {r} of key {key}")
             flat.extend(int(t.data_ptr()) for t in g)
         self.ptrs = (ctypes.c_void_p * max(len(flat), 1))(*flat)
         self._keep = grads
@@ -294,10 +317,16 @@ class KVStore:
             raise KVError(rc, self._L.kv_last_error(self._h).decode())
 
     # --- values
+    def _check_f32(self, key: int, t, what: str) -> None:
+        if 0 <= key < len(self.key_numel):                 # an unknown key is the library's to refuse
+            check_tensor(t, self.key_numel[key], KV_F32, f"{what} of key {key}")
+
     def set_weights(self, key: int, src) -> None:
+        self._check_f32(key, src, "initial weights")
         self._check(self._L.kv_set_weights(self._h, key, ctypes.c_void_p(src.data_ptr())))
 
     def set_momentum(self, key: int, src) -> None:
+        self._check_f32(key, src, "momentum")
         self._check(self._L.kv_set_momentum(self._h, key, ctypes.c_void_p(src.data_ptr())))
 
     def set_lr(self, lr: float) -> None:
@@ -317,6 +346,9 @@ class KVStore:
     def push(self, key: int, grads: Sequence) -> None:
         if len(grads) != self.W:
             raise ValueError(f"expected {self.W} gradient copies")
+        if 0 <= key < len(self.key_numel):
+            for r, g in enumerate(grads):
+                check_tensor(g, self.key_numel[key], self.grad_dtype, f"gradient copy {r} of key {key}")
         ptrs = (ctypes.c_void_p * self.W)(*[int(g.data_ptr()) for g in grads])
         self._check(self._L.kv_push(self._h, key, ptrs))
 
@@ -326,7 +358,7 @@ class KVStore:
         return self._L.kv_push(self._h, key, arr)
 
     def make_push_list(self, keys: Sequence[int], grads: Sequence[Sequence]) -> PushList:
-        return PushList(self.W, keys, grads)
+        return PushList(self.W, keys, grads, self.key_numel, self.grad_dtype)
 
     def push_list(self, pl: PushList) -> None:
         self._check(self._L.kv_push_list(self._h, pl.n, pl.keys, pl.ptrs))
@@ -347,18 +379,25 @@ class KVStore:
 
     # --- pull
     def pull(self, key: int, out) -> None:
+        self._check_f32(key, out, "pull destination")
         self._check(self._L.kv_pull(self._h, key, ctypes.c_void_p(out.data_ptr())))
 
     def pull_list(self, keys: Sequence[int], outs: Sequence) -> None:
         n = len(keys)
+        if len(outs) != n:
+            raise ValueError("one destination per key expected")
+        for k, o in zip(keys, outs):
+            self._check_f32(int(k), o, "pull destination")
         karr = (ctypes.c_int * max(n, 1))(*[int(k) for k in keys])
         parr = (ctypes.c_void_p * max(n, 1))(*[int(o.data_ptr()) for o in outs])
         self._check(self._L.kv_pull_list(self._h, n, karr, parr))
 
     def pull_grad(self, key: int, out) -> None:
+        self._check_f32(key, out, "pull destination")
         self._check(self._L.kv_pull_grad(self._h, key, ctypes.c_void_p(out.data_ptr())))
 
     def pull_momentum(self, key: int, out) -> None:
+        self._check_f32(key, out, "pull destination")
         self._check(self._L.kv_pull_momentum(self._h, key, ctypes.c_void_p(out.data_ptr())))
 
     def weights_ptr(self, key: int) -> int:
@@ -374,6 +413,10 @@ class KVStore:
 
     def set_broadcast(self, key: int, replicas: Sequence, dtype="f32") -> None:
         """kv_set_broadcast: replicas is a list of tensors (or raw addresses) that receive the key's new weights."""
+        code = _dtype_code(dtype)
+        for i, r in enumerate(replicas):
+            if not isinstance(r, int) and 0 <= key < len(self.key_numel):
+                check_tensor(r, self.key_numel[key], code, f"replica {i} of key {key}")
         ptrs = [int(r) if isinstance(r, int) else int(r.data_ptr()) for r in replicas]
         arr = (ctypes.c_void_p * max(len(ptrs), 1))(*ptrs)
         self._check(self._L.kv_set_broadcast(self._h, key, len(ptrs), arr, _dtype_code(dtype)))

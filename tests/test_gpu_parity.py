@@ -119,7 +119,7 @@ def test_one_key_beyond_four_gigabytes(dtype, numel, W):
 
 # ------------------------------------------------------------------ ragged sizes, every W path
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
-@pytest.mark.parametrize("W", [1, 2, 3, 4, 5, 7, 8, 9, 13, 16, 32, 33])
+@pytest.mark.parametrize("W", [1, 2, 3, 4, 5, 7, 8, 9, 13, 15, 16, 17, 24, 32, 33, 40, 64, 100])
 @pytest.mark.parametrize("order", [orc.SEQUENTIAL, orc.PAIRWISE])
 def test_ragged_keys_all_rank_counts(dtype, W, order):
     pair = Pair(RAGGED, W, dtype, 16 << 10, lr=0.1, momentum=0.9, wd=1e-4, order=order)
@@ -660,3 +660,26 @@ def test_init_rejects_bad_arguments():
         kv.KVStore([10, -5], 2, "f32", 4096, lr=0.1)
     with pytest.raises(kv.KVError):
         kv.KVStore([10], 2, "f32", 0, lr=0.1)
+
+
+def test_tuning_values_round_trip_and_bad_ones_are_refused():
+    import paper_1802_06949_amd as kv
+    want = dict(unroll=2, workgroups_per_cu=3, nontemporal=5, xcd_remap=128, lane_elems=2, resident_workgroups=6)
+    st = kv.KVStore([1000, 5000], 4, "f32", 1 << 12, lr=0.1, **want)
+    try:
+        got, settled = st.get_tuning()
+        assert got == want and settled
+    finally:
+        st.close()
+    st = kv.KVStore([1000, 5000], 4, "f32", 1 << 12, lr=0.1)            # defaults resolved, never the "default" codes
+    try:
+        got, _ = st.get_tuning()
+        assert got["unroll"] == 1 and got["lane_elems"] in (1, 2, 4) and got["nontemporal"] in (9, 13)
+        assert got["workgroups_per_cu"] == 0 and got["xcd_remap"] in (64, 1024) and got["resident_workgroups"] in (0, 3, 4, 5, 6, 7, 8)
+    finally:
+        st.close()
+    for bad in (dict(workgroups_per_cu=65), dict(xcd_remap=(1 << 20) + 1), dict(resident_workgroups=2), dict(resident_workgroups=9),
+                dict(resident_workgroups=-1), dict(nontemporal=2), dict(lane_elems=3), dict(lane_elems=2, unroll=4)):
+        with pytest.raises(kv.KVError) as e:
+            kv.KVStore([1000], 4, "f32", 1 << 12, lr=0.1, **bad)
+        assert e.value.status == -1, bad

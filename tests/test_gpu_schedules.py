@@ -115,6 +115,38 @@ def test_concurrent_pull_then_barrier_sees_the_update():
         pair.close()
 
 
+@pytest.mark.parametrize("schedule", [(CONCURRENT, 4, 0), (CHAINED, 1, 0)], ids=["concurrent", "chained"])
+def test_wait_for_one_key_covers_its_launch_and_its_pulls(schedule):
+    """kv_wait(key) waits for the event of that key's last launch (or of a pull issued after it), not for the
+    stream: what the key's pull wrote must be complete when it returns, under per-key launches on several
+    streams and under per-unit launches on one stream."""
+    import torch
+    numel = [1 << 20, 300, 1 << 19, 70000, 5, 1 << 20]
+    pair = Pair(numel, 4, "f32", 64 << 10, lr=0.5, momentum=0.9, wd=0.0, schedule=schedule)
+    try:
+        pair.set_weights([_rng(60, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        host = [torch.empty(n, dtype=torch.float32).pin_memory() for n in numel]
+        for t in range(3):
+            g = _grads(numel, 4, "f32", 61 + t)
+            dev = pair.upload(g)
+            outs = [torch.zeros(n, device="cuda") for n in numel]
+            torch.cuda.synchronize()
+            for k in range(len(numel)):
+                pair.gpu.push(k, dev[k])
+                pair.gpu.pull(k, outs[k])
+            pair.cpu.step(g)
+            side = torch.cuda.Stream()
+            for k in reversed(range(len(numel))):
+                pair.gpu.wait(k)
+                with torch.cuda.stream(side):          # a stream that is ordered after nothing of the store's
+                    host[k].copy_(outs[k], non_blocking=True)
+                side.synchronize()
+                assert np.array_equal(host[k].numpy().view(np.uint32), pair.cpu.w[k].view(np.uint32)), f"step {t} key {k}"
+            pair.gpu.wait()
+    finally:
+        pair.close()
+
+
 def test_lazy_store_merges_single_pushes_into_one_launch():
     """The paper's Dependency Chaining loop: all pushes first, then the pulls.  With
     KV_FLAG_LAZY_LAUNCH the single pushes pile up and the whole iteration is one launch."""

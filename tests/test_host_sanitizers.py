@@ -43,6 +43,18 @@ def test_oracle_under_asan_ubsan(tmp_path):
 
 
 @pytest.mark.skipif(not os.path.exists(os.path.join(HIP_INC, "hip", "hip_runtime_api.h")), reason="needs the HIP headers")
+def test_store_steady_state_allocates_nothing(tmp_path):
+    """The whole host side of the store (kv_store.cpp + kv_plan.cpp) against a stand-in HIP runtime, under
+    AddressSanitizer + UBSan, with every operator new and every allocating runtime call counted."""
+    out = _build_and_run(tmp_path, "alloc_count",
+                         ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                          "-D__HIP_PLATFORM_AMD__", "-I", HIP_INC, "-I", CSRC, "-I", INC,
+                          os.path.join(NATIVE, "alloc_count.cpp"), os.path.join(NATIVE, "hip_stub.cpp"),
+                          os.path.join(CSRC, "kv_store.cpp"), os.path.join(CSRC, "kv_plan.cpp")])
+    assert "allocates nothing: ok" in out
+
+
+@pytest.mark.skipif(not os.path.exists(os.path.join(HIP_INC, "hip", "hip_runtime_api.h")), reason="needs the HIP headers")
 def test_engine_under_thread_sanitizer(tmp_path):
     env = dict(os.environ, LD_LIBRARY_PATH="/opt/rocm/lib:" + os.environ.get("LD_LIBRARY_PATH", ""))
     out = _build_and_run(tmp_path, "engine_fuzz",

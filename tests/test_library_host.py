@@ -179,3 +179,42 @@ def test_headers_are_valid_c_and_cxx(tmp_path):
                 ["g++", "-std=c++17", "-x", "c++", "-Wall", "-Wextra", "-Werror", "-fsyntax-only"]):
         r = subprocess.run(cmd + ["-I", inc, str(src)], capture_output=True, text=True)
         assert r.returncode == 0, r.stderr
+
+
+# ------------------------------------------------------------------ the binding's host-side bounds checks
+class _FakeTensor:
+    """Carries what the binding looks at before it takes data_ptr()."""
+
+    def __init__(self, numel, dtype="torch.float32", cuda=True, contiguous=True):
+        self._n, self.dtype, self.is_cuda, self._c = numel, dtype, cuda, contiguous
+
+    def numel(self):
+        return self._n
+
+    def is_contiguous(self):
+        return self._c
+
+    def data_ptr(self):
+        return 4096
+
+
+def test_binding_refuses_tensors_that_do_not_match_the_key():
+    import torch
+    ok = _FakeTensor(100)
+    kv.check_tensor(ok, 100, kv.KV_F32, "x")
+    for bad, needle in [(_FakeTensor(99), "99 elements"), (_FakeTensor(100, "torch.float16"), "dtype"),
+                        (_FakeTensor(100, cuda=False), "GPU memory"), (_FakeTensor(100, contiguous=False), "contiguous"),
+                        (torch.zeros(100), "GPU memory")]:
+        with pytest.raises(ValueError, match=needle):
+            kv.check_tensor(bad, 100, kv.KV_F32, "x")
+    with pytest.raises(ValueError, match="dtype"):
+        kv.check_tensor(_FakeTensor(100), 100, kv.KV_F16, "x")
+    # a push list checks every copy of every key against the key's size and the store's gradient dtype
+    numel = [100, 7]
+    kv.PushList(2, [0, 1], [[_FakeTensor(100)] * 2, [_FakeTensor(7)] * 2], numel, kv.KV_F32)
+    with pytest.raises(ValueError, match="gradient copy 1 of key 1"):
+        kv.PushList(2, [0, 1], [[_FakeTensor(100)] * 2, [_FakeTensor(7), _FakeTensor(8)]], numel, kv.KV_F32)
+    with pytest.raises(ValueError, match="dtype"):
+        kv.PushList(2, [1], [[_FakeTensor(7)] * 2], numel, kv.KV_F16)
+    with pytest.raises(ValueError, match="2 gradient copies"):
+        kv.PushList(2, [1], [[_FakeTensor(7)]], numel, kv.KV_F32)

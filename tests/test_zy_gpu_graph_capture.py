@@ -233,3 +233,43 @@ def test_lazy_store_captures_single_pushes_as_one_launch():
             assert pulled.abs().sum().item() > 0
         finally:
             pair.close()
+
+
+def test_captured_list_pull_survives_reuse_of_every_staging_chunk():
+    """A list pull recorded into a graph must not depend on pinned staging memory: between replays, eager list pulls
+    with other destinations and steps with new gradient buffers (pointer-table uploads) use every staging chunk
+    several times over; each replay still has to put the right weights into the captured destinations."""
+    import torch
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        pair = _pair(s)
+        try:
+            K = len(NUMEL)
+            keys = list(range(K))
+            gA = _grads(21)
+            dA = pair.upload(gA)
+            pair.step(gA, dev=dA)                                  # the buffers' pointers now sit in a cached table
+            plA = pair.gpu.make_push_list(keys, dA)
+            outs = [torch.zeros(n, dtype=torch.float32, device="cuda") for n in NUMEL]
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=s):
+                pair.gpu.push_list(plA)
+                pair.gpu.pull_list(keys, outs)
+            s.synchronize()
+            pair.compare("a capture runs nothing")
+            for i in range(3):
+                for j in range(10):                                # 20 uses of the 8 staging chunks
+                    other = [torch.zeros(n, dtype=torch.float32, device="cuda") for n in NUMEL]
+                    pair.gpu.pull_list(keys, other)
+                    pair.step(_grads(100 + 10 * i + j))
+                pair.compare(f"eager churn {i}")
+                for o in outs:
+                    o.fill_(-1.0)
+                graph.replay()
+                pair.cpu.step(gA)
+                pair.gpu.wait()
+                pair.compare(f"replay {i}")
+                for k in keys:
+                    assert np.array_equal(outs[k].cpu().numpy().view(np.uint32), pair.cpu.w[k].view(np.uint32)), f"replay {i} key {k}"
+        finally:
+            pair.close()
