@@ -32,7 +32,7 @@ METRIC = "aggregated gradient bytes/s (GB/s, % HBM peak) for W-way reduce+SGD up
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=6000)
+    ap.add_argument("--steps", type=int, default=0, help="timed steps (default 6000; 30 with --overlap)")
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..5 (3 = ResNet-50-shaped, W=8)")
     ap.add_argument("--ranks", type=int, default=0, help="override the configuration's W (characterisation runs)")
@@ -42,6 +42,8 @@ def parse_args():
     ap.add_argument("--cold-steps", type=int, default=40,
                     help="steps of the cold-state legs: before each one a plain pass over 1 GiB of unrelated memory "
                          "flushes L2 and the memory-side cache, outside the step's event pair (0 = skip)")
+    ap.add_argument("--cold-evict", choices=["both", "clean", "dirty"], default="both",
+                    help="which cold-state legs run (profiling runs that want one kind of launch in the trace)")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the legs on the other benchmark configurations (1, 2, 4, 5 and 6)")
     ap.add_argument("--cpu-seconds", type=float, default=8.0,
@@ -65,6 +67,12 @@ def parse_args():
                          "stream, reported as backward only / aggregation only / serial / overlapped")
     ap.add_argument("--spin", type=int, default=20000, help="--overlap: multiply-adds per lane of the largest producer")
     ap.add_argument("--engine-threads", type=int, default=2)
+    ap.add_argument("--producer-workgroups", type=int, default=0,
+                    help="--overlap: cap of every producer's grid (0 = up to 2048 workgroups, which fill the chip; 256 = "
+                         "one workgroup of 256 lanes per compute unit)")
+    ap.add_argument("--producer-bytes", type=int, default=0,
+                    help="--overlap: a producer copies only this many leading bytes of its gradient (0 = all of it), so that "
+                         "it spends its time computing")
     ap.add_argument("--flat-grads", action="store_true",
                     help="each rank's gradients of all keys live in ONE buffer (keys at 256-byte aligned offsets) "
                          "instead of one allocation per key and rank")
@@ -279,7 +287,9 @@ def cpu_baseline(cfg, weights, grads_host, seconds: float):
 
 
 def overlap_mode(args) -> int:
-    """Overlap of aggregation with (synthetic) backward compute, the paper's actual claim."""
+    """Overlap of aggregation with (synthetic) backward compute, the paper's actual claim.  The fused kernel can be
+    confined to part of the chip (--workgroups-per-cu: a persistent grid of that many workgroups per compute unit)
+    and the producers can leave wave slots free (--producer-workgroups) and be compute bound (--producer-bytes)."""
     import numpy as np
     import torch
     import workloads as wl
@@ -291,16 +301,18 @@ def overlap_mode(args) -> int:
     K, W = len(cfg.keys), cfg.W
     tdt = torch.float32 if cfg.grad_dtype == "f32" else torch.float16
     store = kv.KVStore(cfg.numel, W, cfg.grad_dtype, cfg.bucket_bytes, lr=cfg.lr, momentum=cfg.momentum, wd=cfg.wd,
-                       descending=True)
-    grads = wl.make_step_gradients(cfg, 0, args.gen_threads)
-    staged = [torch.from_numpy(np.stack(g)).cuda() for g in grads]
-    live = [torch.zeros_like(s) for s in staged]
-    del grads
+                       descending=True, workgroups_per_cu=args.workgroups_per_cu, lane_elems=args.lane_elems,
+                       unroll=args.unroll, resident_workgroups=args.resident_workgroups)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+    staged = [(torch.randn(W, n, device="cuda", generator=gen) * 1e-3).to(tdt) for n in cfg.numel]
+    live = [s.clone() for s in staged]                   # valid gradients even where a producer copies only a part
     side = torch.cuda.Stream()
     eng = Engine(args.engine_threads)
     biggest = max(cfg.numel)
     spin = [int(args.spin * n / biggest) for n in cfg.numel]
-    loop = EngineLoop(store, eng, staged, live, side.cuda_stream, spin)
+    loop = EngineLoop(store, eng, staged, live, side.cuda_stream, spin, max_workgroups=args.producer_workgroups,
+                      copy_bytes_cap=args.producer_bytes)
     lists = store.make_push_list(list(range(K - 1, -1, -1)), [[live[k][r] for r in range(W)] for k in range(K - 1, -1, -1)])
 
     def timed(fn, reps):
@@ -323,16 +335,28 @@ def overlap_mode(args) -> int:
         loop.step()
         store.wait()
 
+    def one_launch_behind():
+        # the producers of this iteration run while the ONE merged launch of the previous iteration's gradients does
+        # (double-buffered gradients in a real loop; here the same buffers, which the producers rewrite with the same values)
+        store.push_list(lists)
+        loop.backward_only()
+        side.synchronize()
+        store.wait()
+
     reps = args.steps
     res = {
         "mode": "overlap",
         "workload": cfg.name,
         "spin": args.spin,
         "engine_threads": args.engine_threads,
+        "producer_workgroups": args.producer_workgroups or 2048,
+        "producer_bytes": args.producer_bytes or "all",
+        "fused_workgroups_per_cu": store.get_tuning()[0]["workgroups_per_cu"],
         "backward_only_ms": round(timed(lambda: (loop.backward_only(), side.synchronize()), reps), 4),
         "aggregation_only_ms": round(timed(lambda: (store.push_list(lists), store.wait()), reps), 4),
         "serial_ms": round(timed(serial, reps), 4),
         "overlapped_ms": round(timed(overlapped, reps), 4),
+        "merged_launch_beside_next_backward_ms": round(timed(one_launch_behind, reps), 4),
     }
     loop.close()
     eng.close()
@@ -343,6 +367,8 @@ def overlap_mode(args) -> int:
 
 def main() -> int:
     args = parse_args()
+    if args.steps <= 0:
+        args.steps = 30 if args.overlap else 6000
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (the W gradient replicas sit in one MI355X's HBM); "
               f"--gpus {args.gpus} is not supported", file=sys.stderr)
@@ -549,7 +575,32 @@ def main() -> int:
                 rd, wr = bufs[:n_read], bufs[n_read:n_read + n_write]
                 ceil[f"mix_{n_read}r_{n_write}w_{label}_GBps"] = rate(lambda: kv.stream_mix(rd, wr, per),
                                                                      (n_read + n_write) * per, reps=10)
-        del pool
+        # The same 16 read streams and 2 written streams, but the writes come from a second kernel on a second
+        # stream that starts together with the reader and finishes early: the writes reach DRAM bunched in time
+        # instead of spread evenly over the reads (19 x 512 MiB moved in all: the writer also reads one buffer).
+        bufs = [b[i * 4096:i * 4096 + per] for i, b in enumerate(pool)]
+        extra_rd = torch.zeros(per, dtype=torch.uint8, device="cuda")
+        side2 = torch.cuda.Stream()
+        fork, e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(4))
+        best = None
+        for _ in range(4):
+            torch.cuda.synchronize()
+            cur = torch.cuda.current_stream()
+            fork.record(cur)
+            side2.wait_event(fork)
+            with torch.cuda.stream(side2):
+                kv.stream_mix([extra_rd], bufs[16:18], per, stream=side2.cuda_stream)
+                e1.record(side2)
+            kv.stream_mix(bufs[:16], [], per)
+            e2.record(cur)
+            torch.cuda.synchronize()
+            t = max(fork.elapsed_time(e1), fork.elapsed_time(e2)) * 1e-3
+            best = t if best is None or t < best else best
+        ceil["concurrent_16r_kernel_and_1r_2w_kernel_GBps"] = round(19 * per / best / 1e9, 1)
+        ceil["same_two_kernels_one_after_the_other_GBps"] = round(
+            19 * per / (16 * per / (ceil["mix_16r_0w_staggered_4KB_GBps"] * 1e9) +
+                        3 * per / rate(lambda: kv.stream_mix([extra_rd], bufs[16:18], per), 3 * per, reps=10) / 1e9) / 1e9, 1)
+        del pool, extra_rd
         extra["ceilings"] = ceil
 
     if args.calib_copy > 0:
@@ -569,8 +620,10 @@ def main() -> int:
     if plain and (args.cold_steps > 0 or not args.no_other_configs):
         evict_buf = torch.zeros(EVICT_BYTES // 4, dtype=torch.float32, device="cuda")
     if plain and args.cold_steps > 0:
-        cold = cold_leg(kv, store, do_step, args.cold_steps, evict_buf, False, alg_bytes_step)
-        cold_dirty = cold_leg(kv, store, do_step, args.cold_steps, evict_buf, True, alg_bytes_step)
+        if args.cold_evict in ("both", "clean"):
+            cold = cold_leg(kv, store, do_step, args.cold_steps, evict_buf, False, alg_bytes_step)
+        if args.cold_evict in ("both", "dirty"):
+            cold_dirty = cold_leg(kv, store, do_step, args.cold_steps, evict_buf, True, alg_bytes_step)
     floor_us = launch_floor_us(kv)
     state_bytes = 8 * N
     grad_bytes = N * cfg.W * itemsize

@@ -70,7 +70,9 @@ int  kv_engine_stats(const kv_engine* engine, int64_t* ops_run_out, int* max_con
 /* Stand-in for a backward operator that produces a gradient: on hip_stream every lane first
  * runs `spin` (>= 0) dependent multiply-adds (compute without memory traffic), then `bytes`
  * bytes (multiple of 16, both pointers 16-byte aligned) are copied from src to dst, then
- * record_event (may be NULL) is recorded on that stream. */
+ * record_event (may be NULL) is recorded on that stream.  max_workgroups caps the kernel's grid
+ * (workgroups of 256 lanes; 0 = as many as the copy needs, at most 2048, which fills every compute
+ * unit): 256 or 512 leave most wave slots of the chip to whatever else is running. */
 typedef struct kv_op_copy_args {
     void*       dev_dst;
     const void* dev_src;
@@ -79,6 +81,7 @@ typedef struct kv_op_copy_args {
     void*       record_event;   /* hipEvent_t or NULL */
     int         spin;
     int         status;
+    int         max_workgroups;
 } kv_op_copy_args;
 void kv_op_copy(void* arg /* kv_op_copy_args* */);
 

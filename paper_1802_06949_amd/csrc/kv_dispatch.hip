@@ -182,11 +182,12 @@ hipError_t kv_launch_read(const void* src, size_t bytes, hipStream_t stream) {
     return hipGetLastError();
 }
 
-hipError_t kv_launch_busy_copy(void* dst, const void* src, size_t bytes, int spin, hipStream_t stream) {
+hipError_t kv_launch_busy_copy(void* dst, const void* src, size_t bytes, int spin, int max_blocks, hipStream_t stream) {
     const size_t nvec = bytes / 16;
     if (nvec == 0) return hipSuccess;
     size_t blocks = (nvec + KV_THREADS - 1) / KV_THREADS;
-    if (blocks > 256u * 8u) blocks = 256u * 8u;
+    const size_t cap = max_blocks > 0 && max_blocks < 256 * 8 ? (size_t)max_blocks : 256u * 8u;
+    if (blocks > cap) blocks = cap;
     hipLaunchKernelGGL(kv_busy_copy_kernel, dim3((unsigned)blocks), dim3(KV_THREADS), 0, stream,
                        static_cast<f32x4*>(dst), static_cast<const f32x4*>(src), nvec, spin);
     return hipGetLastError();

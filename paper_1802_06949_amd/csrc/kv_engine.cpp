@@ -237,11 +237,11 @@ void kv_op_copy(void* arg) {
     kv_op_copy_args* a = static_cast<kv_op_copy_args*>(arg);
     if (!a) return;
     if (!a->dev_dst || !a->dev_src || (a->bytes & 15u) || ((uintptr_t)a->dev_dst & 15u) || ((uintptr_t)a->dev_src & 15u) ||
-        a->spin < 0) {
+        a->spin < 0 || a->max_workgroups < 0) {
         a->status = KV_ERR_ARG;
         return;
     }
-    a->status = kv_launch_busy_copy(a->dev_dst, a->dev_src, a->bytes, a->spin, static_cast<hipStream_t>(a->hip_stream)) ==
+    a->status = kv_launch_busy_copy(a->dev_dst, a->dev_src, a->bytes, a->spin, a->max_workgroups, static_cast<hipStream_t>(a->hip_stream)) ==
                         hipSuccess
                     ? KV_OK
                     : KV_ERR_HIP;

@@ -21,7 +21,8 @@ hipError_t kv_launch_copy(void* dst, const void* src, size_t bytes, hipStream_t 
 
 // Copy preceded by `spin` dependent multiply-adds per lane (a compute-bound stand-in for a
 // backward operator).
-hipError_t kv_launch_busy_copy(void* dst, const void* src, size_t bytes, int spin, hipStream_t stream);
+// The grid has at most max_blocks workgroups (0 = at most 2048).
+hipError_t kv_launch_busy_copy(void* dst, const void* src, size_t bytes, int spin, int max_blocks, hipStream_t stream);
 
 // Copies the keys whose tiles are [tile_lo, tile_hi) from an arena to dst_table[segment] (device
 // table of one destination pointer per segment), one workgroup per tile.

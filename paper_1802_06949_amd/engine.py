@@ -15,7 +15,7 @@ class CopyArgs(ctypes.Structure):
     """kv_op_copy_args"""
     _fields_ = [("dev_dst", ctypes.c_void_p), ("dev_src", ctypes.c_void_p), ("bytes", ctypes.c_size_t),
                 ("hip_stream", ctypes.c_void_p), ("record_event", ctypes.c_void_p), ("spin", ctypes.c_int),
-                ("status", ctypes.c_int)]
+                ("status", ctypes.c_int), ("max_workgroups", ctypes.c_int)]
 
 
 class PushArgs(ctypes.Structure):

@@ -15,10 +15,12 @@ from .kvstore import KVError, KVStore
 
 class EngineLoop:
     def __init__(self, store: KVStore, engine: Engine, staged: Sequence, live: Sequence, producer_stream: int,
-                 spin: Sequence[int]):
+                 spin: Sequence[int], max_workgroups: int = 0, copy_bytes_cap: int = 0):
         """staged[k], live[k]: device tensors of shape [W, numel_k] (contiguous); the producer of key k
         copies staged[k] to live[k] on producer_stream after spin[k] multiply-adds per lane; the store
-        reads rank r of key k at live[k][r]."""
+        reads rank r of key k at live[k][r].  max_workgroups caps every producer's grid (0 = it fills the
+        chip); copy_bytes_cap > 0 makes a producer copy only that many leading bytes, i.e. spend nearly all
+        of its time computing (live must then hold valid gradients already)."""
         self.store, self.engine = store, engine
         K = len(live)
         self.K = K
@@ -31,8 +33,10 @@ class EngineLoop:
         W = store.W
         for k in range(K):
             nbytes = live[k].numel() * live[k].element_size()
+            if copy_bytes_cap > 0:
+                nbytes = min(nbytes, copy_bytes_cap) // 16 * 16
             self.copy_args.append(CopyArgs(live[k].data_ptr(), staged[k].data_ptr(), nbytes, producer_stream,
-                                           self.events[k], int(spin[k]), 0))
+                                           self.events[k], int(spin[k]), 0, int(max_workgroups)))
             ptrs = (ctypes.c_void_p * W)(*[live[k][r].data_ptr() for r in range(W)])
             evs = (ctypes.c_void_p * 1)(self.events[k])
             self._keep += [ptrs, evs]
