@@ -575,32 +575,7 @@ def main() -> int:
                 rd, wr = bufs[:n_read], bufs[n_read:n_read + n_write]
                 ceil[f"mix_{n_read}r_{n_write}w_{label}_GBps"] = rate(lambda: kv.stream_mix(rd, wr, per),
                                                                      (n_read + n_write) * per, reps=10)
-        # The same 16 read streams and 2 written streams, but the writes come from a second kernel on a second
-        # stream that starts together with the reader and finishes early: the writes reach DRAM bunched in time
-        # instead of spread evenly over the reads (19 x 512 MiB moved in all: the writer also reads one buffer).
-        bufs = [b[i * 4096:i * 4096 + per] for i, b in enumerate(pool)]
-        extra_rd = torch.zeros(per, dtype=torch.uint8, device="cuda")
-        side2 = torch.cuda.Stream()
-        fork, e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(4))
-        best = None
-        for _ in range(4):
-            torch.cuda.synchronize()
-            cur = torch.cuda.current_stream()
-            fork.record(cur)
-            side2.wait_event(fork)
-            with torch.cuda.stream(side2):
-                kv.stream_mix([extra_rd], bufs[16:18], per, stream=side2.cuda_stream)
-                e1.record(side2)
-            kv.stream_mix(bufs[:16], [], per)
-            e2.record(cur)
-            torch.cuda.synchronize()
-            t = max(fork.elapsed_time(e1), fork.elapsed_time(e2)) * 1e-3
-            best = t if best is None or t < best else best
-        ceil["concurrent_16r_kernel_and_1r_2w_kernel_GBps"] = round(19 * per / best / 1e9, 1)
-        ceil["same_two_kernels_one_after_the_other_GBps"] = round(
-            19 * per / (16 * per / (ceil["mix_16r_0w_staggered_4KB_GBps"] * 1e9) +
-                        3 * per / rate(lambda: kv.stream_mix([extra_rd], bufs[16:18], per), 3 * per, reps=10) / 1e9) / 1e9, 1)
-        del pool, extra_rd
+        del pool
         extra["ceilings"] = ceil
 
     if args.calib_copy > 0:

@@ -10,7 +10,7 @@
 extern "C" {
 int kv_copy_bytes(void*, const void*, size_t, void*) { return 0; }
 }
-hipError_t kv_launch_busy_copy(void*, const void*, size_t, int, hipStream_t) { return hipSuccess; }
+hipError_t kv_launch_busy_copy(void*, const void*, size_t, int, int, hipStream_t) { return hipSuccess; }
 extern "C" {
 int kv_push(kv_store*, int, const void* const*) { return 0; }
 int kv_wait_event(kv_store*, void*) { return 0; }
