@@ -32,6 +32,8 @@ struct KvLaunchArgs {
     uint32_t xcd_span;            // tiles of the launch rounded up to whole rows of 8 G (the launch's tiles if G = 0)
     uint32_t lds_pad;             // host side only: bytes of LDS each workgroup reserves and never touches, which
                                   // caps the workgroups resident on a compute unit (0 = no cap)
+    uint32_t grad_align;          // low 4 bits of the OR of every gradient pointer of the launch's segments: a lane
+                                  // width whose vector size divides all of them needs no per-tile alignment check
     float lr, momentum, wd, rescale;
 };
 

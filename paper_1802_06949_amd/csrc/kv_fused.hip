@@ -30,9 +30,10 @@
 #error "KV_TU_W must be defined"
 #endif
 
-// Ranks per batch of the kernel for a W known only at run time.
-#ifndef KV_RUNTIME_W_BATCH
-#define KV_RUNTIME_W_BATCH 8
+// Kernel for a W known only at run time: gradient bytes per lane whose loads are issued back to back
+// (one batch of ranks); the batch is this many bytes divided by the size of a lane's vector.
+#ifndef KV_RUNTIME_W_BYTES
+#define KV_RUNTIME_W_BYTES 128
 #endif
 
 namespace {
@@ -216,6 +217,31 @@ template <int NV> struct FoldSel<NV, true> { using type = FoldPair<NV>; };
 #define KV_CONST __attribute__((address_space(4)))
 #define KV_GLOBAL __attribute__((address_space(1)))
 
+// Placed after the gradient loads of a batch: the instruction scheduler may move nothing across it.  Without it
+// the arithmetic on w and m -- which comes later in program order but depends only on loads issued earlier --
+// has been seen hoisted in front of the gradient loads together with its wait for w and m, which puts two memory
+// round trips one after the other (ResNet-50, 8 fp32 ranks: 169 -> 177 us).
+__device__ __forceinline__ void loads_issued() { __builtin_amdgcn_sched_barrier(0); }
+
+// Ranks r0 .. r0 + RB - 1 (GUARDED: those below W) of one lane's vector: all loads first, then the fold.
+template <bool F16, int N, int RB, bool GUARDED, bool NT, typename Fold>
+__device__ __forceinline__ void fold_batch(Fold& f, const uint64_t KV_CONST* gp, int r0, int W, int64_t boff) {
+    using V = typename Grad<F16, N>::vec;
+    V g[RB];
+#pragma unroll
+    for (int j = 0; j < RB; ++j)
+        if (!GUARDED || r0 + j < W) g[j] = load_grad<NT>((const V KV_GLOBAL*)(gp[r0 + j] + (uint64_t)boff));
+    loads_issued();
+#pragma unroll
+    for (int j = 0; j < RB; ++j) {
+        if (!GUARDED || r0 + j < W) {
+            float t[N];
+            widen<N>(g[j], t);
+            f.push(t);
+        }
+    }
+}
+
 // Sum over ranks of the gradient vector (N values) that starts `boff` bytes into every rank's copy of the key.
 template <bool F16, int N, int WT, bool PAIRWISE, bool NT>
 __device__ __forceinline__ void reduce_vec(const uint64_t KV_CONST* gp, int W, int64_t boff, float (&s)[N]) {
@@ -228,6 +254,7 @@ __device__ __forceinline__ void reduce_vec(const uint64_t KV_CONST* gp, int W, i
             V g[CH];
 #pragma unroll
             for (int j = 0; j < CH; ++j) g[j] = load_grad<NT>((const V KV_GLOBAL*)(gp[r0 + j] + (uint64_t)boff));
+            loads_issued();
 #pragma unroll
             for (int j = 0; j < CH; ++j) {
                 float t[N];
@@ -236,35 +263,15 @@ __device__ __forceinline__ void reduce_vec(const uint64_t KV_CONST* gp, int W, i
             }
         }
     } else {
-        // W known only at run time: whole batches of RB ranks (their loads issued back to back, no
-        // per-rank test), then one guarded batch for the remaining W mod RB ranks; always in rank order.
-        constexpr int RB = KV_RUNTIME_W_BATCH;
+        // W known only at run time: whole large batches (KV_RUNTIME_W_BYTES of gradients per lane in flight),
+        // then whole small batches, then one guarded small batch for what is left; always in rank order.
+        constexpr int RL0 = KV_RUNTIME_W_BYTES / (int)sizeof(V);
+        constexpr int RL = RL0 < 8 ? 8 : RL0 > 32 ? 32 : RL0;
+        constexpr int RS = RL > 8 ? 8 : 4;
         int r0 = 0;
-        for (; r0 + RB <= W; r0 += RB) {
-            V g[RB];
-#pragma unroll
-            for (int j = 0; j < RB; ++j) g[j] = load_grad<NT>((const V KV_GLOBAL*)(gp[r0 + j] + (uint64_t)boff));
-#pragma unroll
-            for (int j = 0; j < RB; ++j) {
-                float t[N];
-                widen<N>(g[j], t);
-                f.push(t);
-            }
-        }
-        if (r0 < W) {
-            V g[RB];
-#pragma unroll
-            for (int j = 0; j < RB; ++j)
-                if (r0 + j < W) g[j] = load_grad<NT>((const V KV_GLOBAL*)(gp[r0 + j] + (uint64_t)boff));
-#pragma unroll
-            for (int j = 0; j < RB; ++j) {
-                if (r0 + j < W) {
-                    float t[N];
-                    widen<N>(g[j], t);
-                    f.push(t);
-                }
-            }
-        }
+        for (; r0 + RL <= W; r0 += RL) fold_batch<F16, N, RL, false, NT>(f, gp, r0, W, boff);
+        for (; r0 + RS <= W; r0 += RS) fold_batch<F16, N, RS, false, NT>(f, gp, r0, W, boff);
+        if (r0 < W) fold_batch<F16, N, RS, true, NT>(f, gp, r0, W, boff);
     }
     f.finish(s);
 }
@@ -407,12 +414,14 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
         }
         struct { int32_t seg, count; int64_t arena_off, seg_off; } td;
         {
-            const int64_t KV_CONST* tw = tiles + (int64_t)t * 4;
-            const int64_t w0 = tw[0];
-            td.seg = (int32_t)(w0 & 0xFFFFFFFF);
-            td.count = (int32_t)(w0 >> 32);
-            td.arena_off = tw[1];
-            td.seg_off = tw[2];
+            // the whole 32-byte descriptor in one scalar load (loaded word by word, the word that is needed last
+            // has been seen fetched by a later, dependent load)
+            typedef int64_t i64x4 __attribute__((ext_vector_type(4)));
+            const i64x4 d = *(const i64x4 KV_CONST*)(tiles + (int64_t)t * 4);
+            td.seg = (int32_t)(d[0] & 0xFFFFFFFF);
+            td.count = (int32_t)(d[0] >> 32);
+            td.arena_off = d[1];
+            td.seg_off = d[2];
         }
         float* __restrict__ wp = a.w + td.arena_off;
         float* __restrict__ mp = a.m + td.arena_off;
@@ -436,8 +445,14 @@ __global__ void __launch_bounds__(KV_THREADS) kv_fused(const KvLaunchArgs a) {
 
         // The vector path needs every gradient pointer aligned to one gradient vector (N elements)
         // and every replica pointer to one replica vector.
-        uint64_t bits = 0;
-        for (int r = 0; r < W; ++r) bits |= gp[r];
+        // The host hands over the OR of all gradient pointers of the launch; only if some buffer of the
+        // launch is misaligned for this lane width does a tile look at its own key's pointers (W dependent
+        // scalar loads when W is known only at run time).
+        uint64_t bits = a.grad_align;
+        if (bits & (uint64_t)(N * sizeof(E) - 1)) {
+            bits = 0;
+            for (int r = 0; r < W; ++r) bits |= gp[r];
+        }
         bool vec_ok = (bits & (uint64_t)(N * sizeof(E) - 1)) == 0;
 
         Bcast bc{nullptr, 0, a.bcast_f16};

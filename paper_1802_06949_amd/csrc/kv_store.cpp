@@ -319,6 +319,12 @@ int launch_tiles(kv_store* st, int s0, int s1, int64_t tile_lo, int64_t tile_hi,
     a.tile_lo = tile_lo;
     a.tile_hi = tile_hi;
     a.W = st->W;
+    {
+        uintptr_t bits = 0;
+        const size_t lo = (size_t)s0 * (size_t)st->W, hi = (size_t)s1 * (size_t)st->W;
+        for (size_t i = lo; i < hi; ++i) bits |= reinterpret_cast<uintptr_t>(st->cur_ptrs[i]);
+        a.grad_align = (uint32_t)(bits & 15u);
+    }
     // a compute unit has 160 KB of LDS: reserving 160 KB / n per workgroup lets n of them be resident
     a.lds_pad = st->resident_wgs >= 3 && st->resident_wgs < 8 ? (uint32_t)((160 * 1024) / st->resident_wgs) & ~1023u : 0u;
     a.lr = st->p.lr;

@@ -200,6 +200,27 @@ def test_random_tuning_on_random_key_sets(seed):
         pair.close()
 
 
+@pytest.mark.parametrize("lane", [1, 2, 4])
+@pytest.mark.parametrize("W,dtype", [(4, "f32"), (5, "f32"), (8, "f16"), (40, "f16"), (33, "f32")])
+def test_one_misaligned_buffer_among_aligned_ones(W, dtype, lane):
+    """The kernel gets the OR of all gradient pointers of a launch and skips its per-key alignment check when
+    that is aligned for its lane width.  Here a single rank of a single key starts one element into its
+    allocation: that key must take the single-element path, every other key the vector path, and both must
+    give the oracle's bits; in the second step no buffer is misaligned."""
+    numel = [700, 2048, 4096 + 3, 12289, 64]
+    pair = Pair(numel, W, dtype, 8 << 10, lr=0.1, momentum=0.9, wd=1e-4, lane_elems=lane)
+    try:
+        pair.set_weights([_rng(5, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        for t in range(2):
+            grads = _grads(numel, W, dtype, 7000 + 10 * W + t)
+            dev = [[to_device(g, 1 if (t == 0 and k == 3 and r == W - 1) else 0) for r, g in enumerate(gk)]
+                   for k, gk in enumerate(grads)]
+            pair.step(grads, dev=dev)
+            pair.compare(f"W={W} {dtype} lane={lane} step {t}")
+    finally:
+        pair.close()
+
+
 @pytest.mark.parametrize("dtype,misalign", [("f32", 1), ("f32", 2), ("f32", 3), ("f16", 1), ("f16", 2), ("f16", 4), ("f16", 7)])
 def test_gradient_buffers_not_16_byte_aligned(dtype, misalign):
     """Views into a flat buffer: aligned to the element only, so the single-element path runs."""
