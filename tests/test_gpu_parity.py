@@ -133,6 +133,25 @@ def test_ragged_keys_all_rank_counts(dtype, W, order):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("lane_elems", [1, 2, 4])
+@pytest.mark.parametrize("W", [3, 5, 9, 12, 15, 17, 20, 31, 33, 36, 40, 47, 63, 64, 65, 72, 100])
+def test_run_time_rank_counts_at_every_lane_width(dtype, lane_elems, W):
+    """The kernel for a W known only at run time folds whole large batches, whole small batches and one guarded
+    batch; the batch sizes depend on the size of a lane's vector (2 to 16 bytes).  Every boundary of that scheme,
+    in both fold orders (pairwise on the odd counts)."""
+    order = orc.PAIRWISE if W % 2 else orc.SEQUENTIAL
+    numel = [1, 255, 1024 + 7, 6000]
+    pair = Pair(numel, W, dtype, 16 << 10, lr=0.1, momentum=0.9, wd=1e-4, order=order, lane_elems=lane_elems)
+    try:
+        pair.set_weights([_rng(9, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        for t in range(2):
+            pair.step(_grads(numel, W, dtype, 9000 + 7 * W + t))
+            pair.compare(f"W={W} {dtype} lane={lane_elems} order={order} step {t}")
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
 @pytest.mark.parametrize("lane_elems,unroll", [(4, 1), (4, 2), (4, 4), (2, 1), (2, 2), (1, 1), (1, 2), (1, 4)])
 @pytest.mark.parametrize("tuning", [dict(), dict(workgroups_per_cu=1), dict(xcd_remap=0), dict(nontemporal=0), dict(nontemporal=1), dict(nontemporal=5), dict(nontemporal=9), dict(nontemporal=13),
                                     dict(workgroups_per_cu=2, xcd_remap=1), dict(workgroups_per_cu=3, xcd_remap=0), dict(xcd_remap=1),
