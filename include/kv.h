@@ -156,7 +156,7 @@ typedef struct kv_tuning {
  * joins the open bucket if the bucket stays <= bucket_bytes, else closes it and
  * opens a new one.  Units are numbered by the id of their first key.  In the
  * weight / momentum arena units lie in index order, keys ascending inside a unit,
- * every key start rounded up to 16 bytes.
+ * every key start rounded up to 256 bytes (64 fp32 elements).
  */
 int     kv_plan_create(kv_plan** out, int num_keys, const int64_t* key_numel /* host [num_keys], each >= 0 */,
                        int grad_dtype, size_t bucket_bytes /* >= 1 */);
@@ -289,7 +289,7 @@ int kv_pull_momentum(kv_store* store, int key, void* dev_out_f32);
  * read again), the list is served key by key as kv_pull would. */
 int kv_pull_list(kv_store* store, int nkeys, const int* keys /* host */, void* const* dev_out_f32 /* host */);
 /* Zero-copy pull: device address of the key's weights inside the arena (numel fp32,
- * 16-byte aligned, valid until kv_destroy; contents change with every step). */
+ * 256-byte aligned, valid until kv_destroy; contents change with every step). */
 int kv_weights_ptr(kv_store* store, int key, void** dev_ptr_out);
 
 /*

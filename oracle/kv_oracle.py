@@ -202,10 +202,11 @@ def plan_units(numel: Sequence[int], grad_itemsize: int, bucket_bytes: int) -> L
     return units
 
 
-def arena_offsets(numel: Sequence[int], units: Sequence[Unit], align_elems: int = 4) -> List[int]:
+def arena_offsets(numel: Sequence[int], units: Sequence[Unit], align_elems: int = 64) -> List[int]:
     """Element offset of every key in the weight / momentum arena: units in
     index order, keys ascending inside a unit, each key start rounded up to a
-    multiple of align_elems (16 bytes of fp32)."""
+    multiple of align_elems (256 bytes of fp32: two 128-byte lines of the GPU's
+    caches; a layout, no arithmetic of the method depends on it)."""
     off = [0] * len(numel)
     cur = 0
     for u in units:

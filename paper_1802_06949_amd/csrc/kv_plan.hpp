@@ -7,6 +7,9 @@
 
 #include "kv_device.hpp"
 
+// Key starts in the w / m / s arenas are multiples of this many elements (256 bytes).
+constexpr int64_t KV_ARENA_ALIGN_ELEMS = 64;
+
 struct KvPlanUnit {
     std::vector<int> keys;   // ascending
     bool large = false;

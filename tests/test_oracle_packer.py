@@ -22,8 +22,11 @@ def test_large_keys_do_not_close_the_open_bucket():
     numel = [10, 300, 5, 256, 20, 1]
     assert _plan(numel, 4, 1024) == [([0, 2, 4, 5], False), ([1], True), ([3], True)]
     units = orc.plan_units(numel, 4, 1024)
-    # unit 0: k0 @0..10, k2 @12..17, k4 @20..40, k5 @40..41; unit 1: k1 @44..344; unit 2: k3 @344
-    assert orc.arena_offsets(numel, units) == [0, 44, 12, 344, 20, 40]
+    # key starts are multiples of 64 elements (256 bytes):
+    # unit 0: k0 @0..10, k2 @64..69, k4 @128..148, k5 @192..193; unit 1: k1 @256..556; unit 2: k3 @576
+    assert orc.arena_offsets(numel, units) == [0, 256, 64, 576, 128, 192]
+    # with 16-byte alignment: k2 @12..17, k4 @20..40, k5 @40..41; k1 @44..344; k3 @344
+    assert orc.arena_offsets(numel, units, align_elems=4) == [0, 44, 12, 344, 20, 40]
 
 
 def test_bucket_closes_on_overflow_and_accepts_exact_fit():
