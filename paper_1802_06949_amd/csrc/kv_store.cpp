@@ -814,8 +814,8 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     // their own (ResNet-50-shaped key set).
     const int64_t state_bytes = 2 * st->plan.arena_numel * (int64_t)sizeof(float);
     const bool resident = state_bytes <= (256LL << 20);
-    // the kernel for any W (it loads eight ranks at a time): measured on the ResNet-50-shaped key set at W = 3, 12, 40, 64
-    int lane = grad_dtype == KV_F16 ? (W < 24 ? 4 : 2) : (W < 8 ? 4 : W < 24 ? 2 : 1);
+    // the kernel for any W: measured on the ResNet-50-shaped key set at W = 3, 12, 24, 40, 64
+    int lane = grad_dtype == KV_F16 ? (W < 24 ? 4 : W < 36 ? 2 : 1) : (W < 8 ? 4 : W < 24 ? 2 : 1);
     {
         static const int w_built[5] = {2, 4, 8, 16, 32};
         static const int lane_f32[5] = {4, 2, 1, 1, 1};
