@@ -51,6 +51,9 @@ def parse_args():
     ap.add_argument("--calib-copy", type=int, default=0, metavar="N",
                     help="also launch the plain copy kernel N times on 1 GiB (byte-counter calibration)")
     ap.add_argument("--ceilings", action="store_true", help="also measure the plain copy kernel on 1 GiB (context)")
+    ap.add_argument("--ceilings-data", choices=["random", "zeros"], default="random",
+                    help="--ceilings: contents of the buffers (on this GPU all-zero buffers move measurably faster "
+                         "than random data; the benchmark's gradients and weights are random)")
     ap.add_argument("--pull-copy", action="store_true", help="also time a copying pull of every key (reported apart)")
     ap.add_argument("--schedule", choices=["chained", "funnel", "concurrent"], default="chained",
                     help="chained = one merged launch per step (headline); funnel / concurrent = one launch per key")
@@ -558,17 +561,21 @@ def main() -> int:
             torch.cuda.synchronize()
             return round(nbytes_moved * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
 
-        ceil = {}
+        def filled(nb):
+            t = torch.zeros(nb, dtype=torch.uint8, device="cuda")
+            return t if args.ceilings_data == "zeros" else t.random_()
+
+        ceil = {"data": args.ceilings_data}
         for label, nb in (("1GiB", 1 << 30), ("96MiB", 96 << 20)):
-            a = torch.zeros(nb, dtype=torch.uint8, device="cuda")
-            b = torch.zeros(nb, dtype=torch.uint8, device="cuda")
+            a = filled(nb)
+            b = filled(nb)
             ceil[f"read_{label}_GBps"] = rate(lambda: kv.read_bytes(a, nb), nb)
             ceil[f"copy_{label}_GBps"] = rate(lambda: kv.copy_bytes(b, a, nb), 2 * nb)
             del a, b
         # mixes of read and written streams of 512 MiB each with the fused kernel's access pattern (nothing
         # fits the memory-side cache), buffers as allocated and staggered by 4 KB per buffer
         per = 512 << 20
-        pool = [torch.zeros(per + 64 * 4096, dtype=torch.uint8, device="cuda") for _ in range(18)]
+        pool = [filled(per + 64 * 4096) for _ in range(18)]
         for label, stagger in (("aligned", 0), ("staggered_4KB", 4096)):
             bufs = [b[i * stagger:i * stagger + per] for i, b in enumerate(pool)]
             for n_read, n_write in ((1, 0), (16, 0), (1, 1), (2, 2), (8, 8), (16, 1), (16, 2)):
