@@ -75,6 +75,23 @@ def test_plan_matches_oracle_scan_on_random_key_sets(seed):
     assert [p.key(k)[1] for k in range(K)] == orc.arena_offsets(numel, ref)
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_keys_start_on_256_byte_boundaries_and_never_overlap(seed):
+    """Stated on its own, not through the oracle's mirror of the layout: every key of the arena starts on a multiple
+    of 64 fp32 elements, keys lie in unit order without overlapping, and the arena ends on such a boundary."""
+    r = _rng(78, seed)
+    K = int(r.integers(1, 80))
+    numel = [int(x) for x in r.choice([0, 1, 3, 10, 63, 64, 65, 100, 1000, 4097, 70001], size=K)]
+    p, units = _lib_plan(numel, "f32", int(r.choice([1, 1024, 1 << 20])))
+    order = [k for keys, _ in units for k in keys]
+    end = 0
+    for k in order:
+        off = p.key(k)[1]
+        assert off % 64 == 0 and off >= end, (k, off, end)
+        end = off + numel[k]
+    assert p.arena_numel >= end and p.arena_numel % 64 == 0
+
+
 def test_plan_rejects_bad_arguments():
     for args in [([], "f32", 1024), ([10, -1], "f32", 1024), ([10], "f32", 0)]:
         with pytest.raises(kv.KVError) as e:
