@@ -89,6 +89,8 @@ struct kv_store {
     kv_sgd_params p{};
     float rescale = 1.0f;
     int unroll = 1, lane_elems = 4, wg_per_cu = 0, nontemporal = 1, xcd_remap = 0, resident_wgs = 0;
+    bool wide_ready = false;                      // a second tile table for 4 elements per lane exists (see launch_tiles)
+    int64_t wide_launches = 0;
     int tile_elems = 0;
     hipStream_t stream = nullptr;
     int device = 0;
@@ -300,15 +302,36 @@ int issue_copy_out(kv_store* st, int key, void* dst, int what, hipStream_t strea
     return KV_OK;
 }
 
-// One fused kernel launch over tiles [tile_lo, tile_hi), which belong to segments [s0, s1).
-int launch_tiles(kv_store* st, int s0, int s1, int64_t tile_lo, int64_t tile_hi, hipStream_t stream, int log_a,
-                 int log_b) {
-    if (tile_hi <= tile_lo) return KV_OK;
+// One fused kernel launch over the tiles of segments [s0, s1).
+//
+// Shape of the launch: the store's (one element per lane for 8 and more fp32 ranks, ...), except when most of the
+// launch's gradient bytes sit in buffers that do not start on a 128-byte line -- views into a flat buffer, say.
+// Every wavefront's 256-byte piece of such a stream straddles a line that its neighbour fetches again (8 fp32
+// ranks: +7 %, 32 ranks: +21 %, 32 fp16 ranks: +31 %); with 4 elements per lane a workgroup covers 4 KB per stream
+// and the shared lines are a quarter as many (+3 %, +4 %, +8 %).  The store keeps a second tile table for that.
+int launch_tiles(kv_store* st, int s0, int s1, hipStream_t stream, int log_a, int log_b) {
+    if (st->ts->seg_tile_begin[(size_t)s1] <= st->ts->seg_tile_begin[(size_t)s0]) return KV_OK;
     const void* const* table = nullptr;
     int rc = table_for(st, s0, s1, stream, &table);
     if (rc != KV_OK) return rc;
+    uintptr_t bits = 0;
+    int64_t off_line = 0, total = 0;
+    for (int sgm = s0; sgm < s1; ++sgm) {
+        uintptr_t row = 0;
+        const size_t lo = (size_t)sgm * (size_t)st->W;
+        for (size_t i = lo; i < lo + (size_t)st->W; ++i) row |= reinterpret_cast<uintptr_t>(st->cur_ptrs[i]);
+        const int64_t n = st->plan.numel[(size_t)st->plan.seg_key[(size_t)sgm]];
+        bits |= row;
+        total += n;
+        if (row & 127u) off_line += n;
+    }
+    const uintptr_t vec4_mask = (uintptr_t)(4 * st->plan.itemsize - 1);
+    const bool wide = st->wide_ready && !st->tuner.active && 2 * off_line > total && (bits & vec4_mask) == 0;
+    const TileSet* ts = wide ? &st->sets[2] : st->ts;
+    const int64_t tile_lo = ts->seg_tile_begin[(size_t)s0], tile_hi = ts->seg_tile_begin[(size_t)s1];
+    if (wide) ++st->wide_launches;
     KvLaunchArgs a{};
-    a.tiles = st->ts->d_tiles;
+    a.tiles = ts->d_tiles;
     a.gptrs = table;
     a.w = st->w;
     a.m = st->m;
@@ -319,12 +342,7 @@ int launch_tiles(kv_store* st, int s0, int s1, int64_t tile_lo, int64_t tile_hi,
     a.tile_lo = tile_lo;
     a.tile_hi = tile_hi;
     a.W = st->W;
-    {
-        uintptr_t bits = 0;
-        const size_t lo = (size_t)s0 * (size_t)st->W, hi = (size_t)s1 * (size_t)st->W;
-        for (size_t i = lo; i < hi; ++i) bits |= reinterpret_cast<uintptr_t>(st->cur_ptrs[i]);
-        a.grad_align = (uint32_t)(bits & 15u);
-    }
+    a.grad_align = (uint32_t)(bits & 15u);
     // a compute unit has 160 KB of LDS: reserving 160 KB / n per workgroup lets n of them be resident
     a.lds_pad = st->resident_wgs >= 3 && st->resident_wgs < 8 ? (uint32_t)((160 * 1024) / st->resident_wgs) & ~1023u : 0u;
     a.lr = st->p.lr;
@@ -336,8 +354,8 @@ int launch_tiles(kv_store* st, int s0, int s1, int64_t tile_lo, int64_t tile_hi,
     sel.W = st->W;
     sel.pairwise = st->p.reduce_order == KV_REDUCE_PAIRWISE;
     sel.keep_sum = (st->flags & KV_FLAG_KEEP_SUM) != 0;
-    sel.unroll = st->unroll;
-    sel.lane_elems = st->lane_elems;
+    sel.unroll = wide ? 1 : st->unroll;
+    sel.lane_elems = wide ? 4 : st->lane_elems;
     sel.nontemporal = st->nontemporal;
     const int64_t ntiles = tile_hi - tile_lo;
     if (ntiles >= (1LL << 31) - 8 * 4096) {
@@ -439,7 +457,7 @@ int launch_run(kv_store* st, int first, int n) {
     }
     const bool record = timed && st->tuner.active;
     if (record) KV_HIP(st, hipEventRecord(st->tuner.e0, st->stream));
-    int rc = launch_tiles(st, s0, s1, st->ts->unit_tile_begin[first], st->ts->unit_tile_begin[first + n], st->stream, first, n);
+    int rc = launch_tiles(st, s0, s1, st->stream, first, n);
     if (rc != KV_OK) return rc;
     if (record) {
         KV_HIP(st, hipEventRecord(st->tuner.e1, st->stream));
@@ -512,7 +530,7 @@ int launch_key(kv_store* st, int key) {
     hipStream_t stream = key_stream(st, key);
     int rc = fork_to(st, stream, lane_of(st, key));
     if (rc != KV_OK) return rc;
-    rc = launch_tiles(st, sgm, sgm + 1, st->ts->seg_tile_begin[sgm], st->ts->seg_tile_begin[sgm + 1], stream, key, 0);
+    rc = launch_tiles(st, sgm, sgm + 1, stream, key, 0);
     if (rc != KV_OK) return rc;
     st->key_serial[(size_t)key] = -1;
     if (st->schedule == KV_SCHED_FUNNEL) {
@@ -893,10 +911,14 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     const bool autotune = (flags & KV_FLAG_AUTOTUNE) != 0;
     const int lane_idx = st->lane_elems == 1 ? 0 : st->lane_elems == 2 ? 1 : 2;
     st->ts = &st->sets[lane_idx];
+    // a store that runs one element per lane by default (not by the caller's choice) also gets the table for four:
+    // launch_tiles switches to it for gradient buffers that are off the 128-byte line grid
+    st->wide_ready = st->lane_elems == 1 && st->unroll == 1 && !(tuning && (tuning->lane_elems != 0 || tuning->unroll != 0));
+    const bool build_set[3] = {lane_idx == 0 || autotune, lane_idx == 1 || autotune, lane_idx == 2 || autotune || st->wide_ready};
     try {
         for (int i = 0; i < 3; ++i) {
             if (i == lane_idx) kv_plan_tiles(st->plan, st->tile_elems, tiles[i], st->sets[i].unit_tile_begin, st->sets[i].seg_tile_begin);
-            else if (autotune) kv_plan_tiles(st->plan, kv_tile_elems(1 << i, 1), tiles[i], st->sets[i].unit_tile_begin, st->sets[i].seg_tile_begin);
+            else if (build_set[i]) kv_plan_tiles(st->plan, kv_tile_elems(1 << i, 1), tiles[i], st->sets[i].unit_tile_begin, st->sets[i].seg_tile_begin);
         }
         st->table_elems = st->plan.seg_key.size() * (size_t)W;
         st->cur_ptrs.assign(st->table_elems, nullptr);
@@ -926,7 +948,7 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
         KV_INIT_HIP(hipMemsetAsync(st->s, 0, arena_bytes, st->stream));
     }
     for (int i = 0; i < 3; ++i) {
-        if (i != lane_idx && !autotune) continue;
+        if (!build_set[i]) continue;
         const size_t tile_bytes = (tiles[i].empty() ? 1 : tiles[i].size()) * sizeof(KvTile);
         KV_INIT_HIP(hipMalloc((void**)&st->sets[i].d_tiles, tile_bytes));
         if (!tiles[i].empty())
@@ -1342,6 +1364,12 @@ int kv_get_tuning(const kv_store* store, kv_tuning* tuning_out, int* tuning_done
     tuning_out->lane_elems = store->lane_elems;
     tuning_out->resident_workgroups = store->resident_wgs;
     if (tuning_done_out) *tuning_done_out = store->tuner.active ? 0 : 1;
+    return KV_OK;
+}
+
+int kv_wide_launches(const kv_store* store, int64_t* count_out) {
+    if (!store || !count_out) return KV_ERR_ARG;
+    *count_out = store->wide_launches;
     return KV_OK;
 }
 

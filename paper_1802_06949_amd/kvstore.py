@@ -95,6 +95,7 @@ def load_library() -> ctypes.CDLL:
     sig("kv_set_schedule", c_int, c_vp, c_int, c_int, c_int)
     sig("kv_barrier", c_int, c_vp)
     sig("kv_get_tuning", c_int, c_vp, P(_Tuning), P(c_int))
+    sig("kv_wide_launches", c_int, c_vp, P(c_i64))
     sig("kv_broadcast_weights", c_int, c_vp, c_int)
     sig("kv_release_captures", c_int, c_vp)
     sig("kv_store_plan", c_vp, c_vp)
@@ -372,6 +373,13 @@ class KVStore:
         t, done = _Tuning(), ctypes.c_int()
         self._check(self._L.kv_get_tuning(self._h, ctypes.byref(t), ctypes.byref(done)))
         return {name: getattr(t, name) for name, _ in _Tuning._fields_}, bool(done.value)
+
+    def wide_launches(self) -> int:
+        """kv_wide_launches: launches that ran four elements per lane because their gradient buffers are off the
+        128-byte line grid."""
+        n = ctypes.c_int64()
+        self._check(self._L.kv_wide_launches(self._h, ctypes.byref(n)))
+        return n.value
 
     def release_captures(self) -> None:
         """Lets the pointer tables that captured launches read be reused (call once the graphs are gone)."""

@@ -240,6 +240,53 @@ def test_one_misaligned_buffer_among_aligned_ones(W, dtype, lane):
         pair.close()
 
 
+@pytest.mark.parametrize("W,dtype", [(8, "f32"), (16, "f32"), (32, "f16"), (40, "f16"), (33, "f32")])
+@pytest.mark.parametrize("mode", ["list", "each"])
+def test_views_off_the_line_grid_take_the_wide_shape_and_the_same_bits(W, dtype, mode):
+    """Gradient views that start 32 bytes off a 128-byte line (but on a 4-element vector): a store whose default
+    is one element per lane launches them with four.  Step 0: all keys off the grid (wide launches); step 1: only a
+    small key off the grid (default shape); step 2: one buffer 4 bytes off (no 4-element vectors: default shape)."""
+    numel = [4096, 300, 40000 + 12, 1024, 70000]
+    isz = 4 if dtype == "f32" else 2
+    pair = Pair(numel, W, dtype, 64 << 10, lr=0.1, momentum=0.9, wd=1e-4)
+    try:
+        assert pair.gpu.get_tuning()[0]["lane_elems"] == 1
+        pair.set_weights([_rng(6, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        wide_before = pair.gpu.wide_launches()
+        for t in range(3):
+            grads = _grads(numel, W, dtype, 8000 + 10 * W + t)
+            def off(k, r):
+                if t == 0:
+                    return 32 // isz
+                if t == 1:
+                    return 32 // isz if k == 1 else 0
+                return 1 if (k == 4 and r == 0) else 32 // isz
+            dev = [[to_device(g, off(k, r)) for r, g in enumerate(gk)] for k, gk in enumerate(grads)]
+            pair.step(grads, dev=dev, mode=mode)
+            pair.compare(f"W={W} {dtype} {mode} step {t}")
+            wide = pair.gpu.wide_launches() - wide_before
+            if t == 0:
+                assert wide >= 1, "buffers off the line grid did not take the wide shape"
+                wide_after_first = wide
+            else:
+                assert wide == wide_after_first or mode == "each", (t, wide, wide_after_first)
+    finally:
+        pair.close()
+
+
+def test_a_fixed_lane_width_is_never_overridden():
+    numel = [4096, 70000]
+    pair = Pair(numel, 8, "f32", 64 << 10, lr=0.1, momentum=0.9, wd=1e-4, lane_elems=1)
+    try:
+        pair.set_weights([_rng(7, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        grads = _grads(numel, 8, "f32", 8100)
+        pair.step(grads, dev=[[to_device(g, 8) for g in gk] for gk in grads])
+        pair.compare("fixed lane width")
+        assert pair.gpu.wide_launches() == 0
+    finally:
+        pair.close()
+
+
 @pytest.mark.parametrize("dtype,misalign", [("f32", 1), ("f32", 2), ("f32", 3), ("f16", 1), ("f16", 2), ("f16", 4), ("f16", 7)])
 def test_gradient_buffers_not_16_byte_aligned(dtype, misalign):
     """Views into a flat buffer: aligned to the element only, so the single-element path runs."""
