@@ -81,6 +81,9 @@ def parse_args():
                          "instead of one allocation per key and rank")
     ap.add_argument("--rank-skew", type=int, default=0,
                     help="--flat-grads: rank r's buffer starts r * this many bytes into its allocation (multiple of 16)")
+    ap.add_argument("--view-offset", type=int, default=0,
+                    help="--flat-grads: every rank's views start this many bytes into its allocation (multiple of 16): "
+                         "32 puts every gradient buffer off the 128-byte line grid")
     ap.add_argument("--graph", action="store_true",
                     help="record one iteration per gradient set into a HIP graph (on a side stream, after eager "
                          "warm-up steps) and time replays of the graphs instead of direct launches")
@@ -420,7 +423,8 @@ def main() -> int:
                 offs.append(cur)
                 cur += (n * itemsize + 255) // 256 * 256 // itemsize
             skew = args.rank_skew // itemsize
-            flats = [torch.empty(cur + cfg.W * skew, dtype=tdt, device="cuda")[r * skew:] for r in range(cfg.W)]
+            voff = args.view_offset // itemsize
+            flats = [torch.empty(cur + cfg.W * skew + voff, dtype=tdt, device="cuda")[r * skew + voff:] for r in range(cfg.W)]
             dset = []
             for k, gk in enumerate(g):
                 row = []
@@ -630,7 +634,8 @@ def main() -> int:
             "units": store.plan.num_units,
             "launches_per_step": launches_per_step,
             "push_mode": args.push_mode + (", replayed from HIP graphs" if args.graph else ""),
-            "tuning": dict(store.get_tuning()[0], self_tuned=args.autotune, settled=store.get_tuning()[1]),
+            "tuning": dict(store.get_tuning()[0], self_tuned=args.autotune, settled=store.get_tuning()[1],
+                           wide_launches=store.wide_launches()),
             "schedule": args.schedule + (f" ({args.streams} streams, barrier every {args.outstanding} keys)"
                                          if args.schedule == "concurrent" else ""),
             "pull": "zero-copy (weights read in place in the arena)" if args.broadcast == "none" else
