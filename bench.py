@@ -251,8 +251,21 @@ def other_config_leg(kv, cfg_id: int, evict_buf, cold_steps: int, floor_us: floa
         "tuning": store.get_tuning()[0],
     }
     if alg < (64 << 20):
+        # the same steps issued by one native loop (kv_push_list_repeat): what a native caller sees, without the
+        # interpreter and the ctypes call between two launches
+        store.push_list_repeat(lists[0], 200)
+        store.wait()
+        store.timing_begin()
+        t0 = time.perf_counter()
+        store.push_list_repeat(lists[0], steps)
+        store.wait()
+        wall_native = time.perf_counter() - t0
+        ev_native, launches_native = store.timing_end()
+        out["native_loop_ms_per_step"] = round(wall_native / steps * 1e3, 5)
+        out["native_loop_avg_launch_us"] = round(ev_native * 1e3 / max(launches_native, 1), 3)
         out["note"] = (f"launch bound and cache resident ({alg / 1e6:.1f} MB per step): the fraction says little; an empty "
-                       f"kernel launch takes {floor_us:.2f} us on this box")
+                       f"kernel launch takes {floor_us:.2f} us on this box.  ms_per_step is a Python loop over the binding "
+                       f"(one ctypes call per step); native_loop_* is the same list push repeated by one native call")
         out["launch_floor_us"] = round(floor_us, 3)
     if state_bytes // 2 > MALL_BYTES:
         out["cold_frac"] = out["algorithmic_frac"]

@@ -44,6 +44,14 @@ int kv_evict_caches(void* dev_buf, size_t bytes, int dirty, void* hip_stream);
  * with events around the call, the floor under any launch-bound step. */
 int kv_null_launch(int count, void* hip_stream);
 
+/* kv_push_list(store, nkeys, keys, dev_grads) `reps` (>= 1) times back to back from native code, the same buffers
+ * every time: the rate at which a native caller can step a launch-bound store, with no interpreter between the
+ * launches (a store of a few hundred KB per step is otherwise timed by its binding).  Stops at the first call that
+ * fails and returns its status. */
+struct kv_store;
+int kv_push_list_repeat(struct kv_store* store, int nkeys, const int* keys /* host */,
+                        const void* const* dev_grads /* host */, int reps);
+
 #ifdef __cplusplus
 }
 #endif

@@ -97,4 +97,16 @@ int kv_null_launch(int count, void* hip_stream) {
     return KV_OK;
 }
 
+int kv_push_list_repeat(kv_store* store, int nkeys, const int* keys, const void* const* dev_grads, int reps) {
+    if (reps < 1) {
+        fail("kv_push_list_repeat: reps must be at least 1");
+        return KV_ERR_ARG;
+    }
+    for (int i = 0; i < reps; ++i) {
+        const int rc = kv_push_list(store, nkeys, keys, dev_grads);
+        if (rc != KV_OK) return rc;
+    }
+    return KV_OK;
+}
+
 }  // extern "C"

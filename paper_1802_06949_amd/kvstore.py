@@ -109,6 +109,7 @@ def load_library() -> ctypes.CDLL:
     sig("kv_stream_mix", c_int, P(c_vp), c_int, c_int, c_sz, c_vp)
     sig("kv_evict_caches", c_int, c_vp, c_sz, c_int, c_vp)
     sig("kv_null_launch", c_int, c_int, c_vp)
+    sig("kv_push_list_repeat", c_int, c_vp, c_int, P(c_int), P(c_vp), c_int)
     sig("kv_last_error", ctypes.c_char_p, c_vp)
     _lib = L
     return L
@@ -363,6 +364,11 @@ class KVStore:
 
     def push_list(self, pl: PushList) -> None:
         self._check(self._L.kv_push_list(self._h, pl.n, pl.keys, pl.ptrs))
+
+    def push_list_repeat(self, pl: PushList, reps: int) -> None:
+        """kv_push_list_repeat (kv_diag.h): the same list push `reps` times from native code, for timing
+        launch-bound stores without the interpreter between the launches."""
+        self._check(self._L.kv_push_list_repeat(self._h, pl.n, pl.keys, pl.ptrs, int(reps)))
 
     def push_list_noalloc(self, pl: PushList) -> None:
         """kv_push_list_noalloc: the list push that allocates and uploads nothing (static device pointer table)."""
