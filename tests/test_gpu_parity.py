@@ -419,6 +419,27 @@ def test_push_order_changes_nothing_and_launches_ascend():
             assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
 
 
+def test_native_repeat_of_a_list_push_is_that_many_steps():
+    """kv_push_list_repeat (a timing helper): n calls of kv_push_list with the same buffers, from native code."""
+    numel = [100, 5000, 0, 1025]
+    pair = Pair(numel, 4, "f32", 8 << 10, lr=0.1, momentum=0.9, wd=1e-4)
+    try:
+        pair.set_weights([_rng(11, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        grads = _grads(numel, 4, "f32", 1100)
+        dev = pair.upload(grads)
+        before = pair.gpu.launch_log(0)[0]
+        pair.gpu.push_list_repeat(pair.gpu.make_push_list(list(range(len(numel))), dev), 3)
+        pair.gpu.wait()
+        assert pair.gpu.launch_log(0)[0] - before == 3
+        for _ in range(3):
+            pair.cpu.step(grads)
+        pair.compare("three native repeats")
+        with pytest.raises(Exception):
+            pair.gpu.push_list_repeat(pair.gpu.make_push_list([0], [dev[0]]), 0)
+    finally:
+        pair.close()
+
+
 def test_list_push_is_one_launch_per_iteration():
     cfg = wl.get_config(2)
     pair = Pair(cfg.numel, cfg.W, "f32", cfg.bucket_bytes, lr=cfg.lr, momentum=cfg.momentum, wd=cfg.wd)
