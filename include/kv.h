@@ -221,8 +221,9 @@ int kv_get_sgd_params(const kv_store* store, kv_sgd_params* params_out /* host *
  * kv_push: hands over the W gradient copies of one key (KVStore API section: a
  * push sums every gradient that carries the same key).  dev_grads: host array of W
  * device pointers, each to numel elements of the gradient dtype, aligned at least
- * to the element size (all W aligned to 16 bytes for fp32, 8 bytes for fp16, selects the
- * vector path).
+ * to the element size (all W aligned to one vector of the launch shape -- at most 16 bytes for
+ * fp32, 8 bytes for fp16 -- selects the vector path; buffers that start on a 128-byte cache line,
+ * as separately allocated arrays do, are read fastest, see kv_wide_launches).
  * The gradients are read in place, asynchronously: they must stay valid and
  * unmodified until kv_wait returns or the stream is synchronised.  Never blocks.
  * When the push completes the next unit in order, that unit and every directly
