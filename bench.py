@@ -192,9 +192,10 @@ def cold_leg(kv, store, do_step, steps: int, evict_buf, dirty: bool, alg_bytes_s
     srt = sorted(iv)
     return {
         "evict": "1 GiB plain read-modify-write pass before every step: caches full of modified unrelated lines, which the "
-                 "step's own allocations force back to memory (worst case)" if dirty else
-                 "1 GiB plain read pass before every step: caches full of clean unrelated lines; w' and m' may end the "
-                 "step in the memory-side cache and be written back later",
+                 "step's own allocations force back to memory inside the timed launch (256 MiB of foreign write-back, about "
+                 "as much as the step leaves modified itself: the steady state with all write-back on the clock)" if dirty else
+                 "1 GiB plain read pass before every step: caches full of clean unrelated lines; the step's own w' and m' end "
+                 "it modified in the memory-side cache and are written back after the timed launch (write-back deferred)",
         "achieved": round(achieved, 2),
         "frac": round(achieved / HBM_PEAK_GBPS, 4),
         "avg_launch_us": round(launch_s * 1e6, 3),
