@@ -102,6 +102,20 @@ def parse_args():
     return ap.parse_args()
 
 
+def kernel_sources_sha256() -> str:
+    """Fingerprint of everything the library is built from (csrc/ and the build script): ties a committed counter
+    summary to the binary that is being timed."""
+    import hashlib
+    h = hashlib.sha256()
+    pkg = os.path.join(ROOT, "paper_1802_06949_amd")
+    files = [os.path.join(pkg, "build.py")] + sorted(os.path.join(pkg, "csrc", f) for f in os.listdir(os.path.join(pkg, "csrc")))
+    for f in files:
+        h.update(os.path.basename(f).encode() + b"\0")
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
 def read_traffic(workload: str):
     """HBM bytes per launch from the committed counter summary of this workload, and where it comes from."""
     name = f"hbm_traffic_{workload}.txt"
@@ -112,7 +126,7 @@ def read_traffic(workload: str):
     with open(path) as f:
         for line in f:
             body = line.lstrip("# ").strip()
-            for tag in ("measured_at_commit", "measured_on"):
+            for tag in ("measured_at_commit", "measured_on", "kernel_sources_sha256"):
                 if body.startswith(tag + ":"):
                     meta[tag] = body.split(":", 1)[1].strip()
             if ":" in line and not line.lstrip().startswith("#"):
@@ -123,6 +137,9 @@ def read_traffic(workload: str):
                     pass
     if "fetch_bytes_per_launch" in vals and "write_bytes_per_launch" in vals:
         meta["note"] = "rocprofv3 FETCH_SIZE / WRITE_SIZE between L2 and the fabric, from that earlier run, not from this one"
+        if "kernel_sources_sha256" in meta:
+            # was the library that run profiled built from the sources this run's library is built from?
+            meta["library_sources_unchanged_since"] = meta.pop("kernel_sources_sha256") == kernel_sources_sha256()
         return vals["fetch_bytes_per_launch"] + vals["write_bytes_per_launch"], meta
     return None, None
 
