@@ -98,6 +98,8 @@ def parse_args():
     ap.add_argument("--workgroups-per-cu", type=int, default=-1)
     ap.add_argument("--nontemporal", type=int, default=-1)
     ap.add_argument("--xcd-remap", type=int, default=-1)
+    ap.add_argument("--run-time-w", action="store_true",
+                    help="run the kernel that takes W at run time even where one built for this W exists")
     ap.add_argument("--gen-threads", type=int, default=min(16, os.cpu_count() or 1))
     return ap.parse_args()
 
@@ -475,7 +477,7 @@ def main() -> int:
     store = kv.KVStore(cfg.numel, cfg.W, cfg.grad_dtype, cfg.bucket_bytes, lr=cfg.lr, momentum=cfg.momentum, wd=cfg.wd,
                        keep_sum=args.keep_sum, lazy=args.lazy, unroll=args.unroll, workgroups_per_cu=args.workgroups_per_cu,
                        nontemporal=args.nontemporal, xcd_remap=args.xcd_remap, lane_elems=args.lane_elems,
-                       resident_workgroups=args.resident_workgroups, autotune=args.autotune)
+                       resident_workgroups=args.resident_workgroups, run_time_w=int(args.run_time_w), autotune=args.autotune)
     for k, w in enumerate(weights):
         if w.size:
             store.set_weights(k, torch.from_numpy(w).cuda())

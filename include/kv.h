@@ -136,6 +136,8 @@ typedef struct kv_sgd_params {
  *                     ranges, one per XCD (so a block of one tile cannot be asked for; 0 deals single tiles);
  *                     G = 2..2^20 = blocks of G consecutive tiles per XCD, never more than an eighth of a launch;
  *                     negative = default (64, or 1024 if w and m do not fit the memory-side cache)
+ *   run_time_w        1 = run the kernel that takes W at run time even where a kernel built for this W exists
+ *                     (W = 2, 4, 8, 16, 32); 0 = default.  For measuring one against the other and for tests.
  * Values outside these ranges make kv_init fail with KV_ERR_ARG; kv_get_tuning returns the values in force.
  */
 typedef struct kv_tuning {
@@ -145,6 +147,7 @@ typedef struct kv_tuning {
     int xcd_remap;
     int lane_elems;
     int resident_workgroups;
+    int run_time_w;
 } kv_tuning;
 
 /* ------------------------------------------------------------------ plan (host only)

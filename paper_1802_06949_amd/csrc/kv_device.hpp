@@ -46,6 +46,7 @@ struct KvKernelSel {
     int unroll;        // vectors per lane and rank: 1, 2, 4
     int lane_elems;    // consecutive elements per vector: 1, 2, 4
     int nontemporal;
+    int generic_w;     // 1: the kernel that takes W at run time, whatever W is
 };
 
 // Elements per tile: every lane owns `unroll` vectors of `lane_elems` consecutive elements,

@@ -8,7 +8,7 @@ hipError_t kv_launch_fused(const KvKernelSel& sel, const KvLaunchArgs& args, uns
 #define KV_CASE(W) \
     case W: return sel.grad_f16 ? kv_launch_fused_f1_w##W(sel, args, grid, stream) \
                                 : kv_launch_fused_f0_w##W(sel, args, grid, stream);
-    switch (sel.W) {
+    switch (sel.generic_w ? 0 : sel.W) {
         KV_CASE(2) KV_CASE(4) KV_CASE(8) KV_CASE(16) KV_CASE(32)
         default: break;
     }

@@ -263,13 +263,21 @@ __device__ __forceinline__ void reduce_vec(const uint64_t KV_CONST* gp, int W, i
             }
         }
     } else {
-        // W known only at run time: whole large batches (KV_RUNTIME_W_BYTES of gradients per lane in flight),
-        // then whole small batches, then one guarded small batch for what is left; always in rank order.
+        // W known only at run time: whole large batches (KV_RUNTIME_W_BYTES of gradients per lane in flight), at
+        // most one batch of half that size, then whole small batches, then one guarded small batch for what is
+        // left; always in rank order.
         constexpr int RL0 = KV_RUNTIME_W_BYTES / (int)sizeof(V);
         constexpr int RL = RL0 < 8 ? 8 : RL0 > 32 ? 32 : RL0;
+        constexpr int RM = RL / 2;                   // 16 .. 31 ranks of 4-byte vectors: one batch of 16 first
         constexpr int RS = RL > 8 ? 8 : 4;
         int r0 = 0;
         for (; r0 + RL <= W; r0 += RL) fold_batch<F16, N, RL, false, NT>(f, gp, r0, W, boff);
+        if constexpr (RM > RS) {
+            if (r0 + RM <= W) {
+                fold_batch<F16, N, RM, false, NT>(f, gp, r0, W, boff);
+                r0 += RM;
+            }
+        }
         for (; r0 + RS <= W; r0 += RS) fold_batch<F16, N, RS, false, NT>(f, gp, r0, W, boff);
         if (r0 < W) fold_batch<F16, N, RS, true, NT>(f, gp, r0, W, boff);
     }

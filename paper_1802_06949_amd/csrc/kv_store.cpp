@@ -89,6 +89,7 @@ struct kv_store {
     kv_sgd_params p{};
     float rescale = 1.0f;
     int unroll = 1, lane_elems = 4, wg_per_cu = 0, nontemporal = 1, xcd_remap = 0, resident_wgs = 0;
+    int generic_w = 0;                            // tuning.run_time_w
     bool wide_ready = false;                      // a second tile table for 4 elements per lane exists (see launch_tiles)
     int64_t wide_launches = 0;
     int tile_elems = 0;
@@ -357,6 +358,7 @@ int launch_tiles(kv_store* st, int s0, int s1, hipStream_t stream, int log_a, in
     sel.unroll = wide ? 1 : st->unroll;
     sel.lane_elems = wide ? 4 : st->lane_elems;
     sel.nontemporal = st->nontemporal;
+    sel.generic_w = st->generic_w;
     const int64_t ntiles = tile_hi - tile_lo;
     if (ntiles >= (1LL << 31) - 8 * 4096) {
         set_err(st->err, "a launch of %lld tiles is beyond the kernel's 32-bit tile index", (long long)ntiles);
@@ -869,6 +871,7 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
         if (tuning->nontemporal >= 0) st->nontemporal = tuning->nontemporal;
         if (tuning->xcd_remap >= 0) st->xcd_remap = tuning->xcd_remap;
         if (tuning->resident_workgroups != 0) st->resident_wgs = tuning->resident_workgroups;
+        st->generic_w = tuning->run_time_w;
     }
     const int nt = st->nontemporal;
     const int le = st->lane_elems, un = st->unroll;
@@ -876,10 +879,11 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
                           (le == 1 && (un == 1 || un == 2 || un == 4));
     if (!shape_ok || !(nt == 0 || nt == 1 || nt == 5 || nt == 9 || nt == 13) ||
         !(st->resident_wgs == 0 || (st->resident_wgs >= 3 && st->resident_wgs <= 8)) ||
-        st->wg_per_cu > 64 || st->xcd_remap > (1 << 20) || (tuning && tuning->resident_workgroups < 0)) {
+        st->wg_per_cu > 64 || st->xcd_remap > (1 << 20) || (tuning && tuning->resident_workgroups < 0) ||
+        (st->generic_w != 0 && st->generic_w != 1)) {
         set_err(g_err, "kv_init: tuning (lane_elems, unroll) must be one of (4,1) (4,2) (4,4) (2,1) (2,2) (1,1) (1,2) (1,4), "
                        "tuning.nontemporal one of 0, 1, 5, 9, 13, tuning.resident_workgroups 0 or 3..8, "
-                       "tuning.workgroups_per_cu at most 64 and tuning.xcd_remap at most 2^20");
+                       "tuning.workgroups_per_cu at most 64, tuning.xcd_remap at most 2^20 and tuning.run_time_w 0 or 1");
         delete st;
         return KV_ERR_ARG;
     }
@@ -1363,6 +1367,7 @@ int kv_get_tuning(const kv_store* store, kv_tuning* tuning_out, int* tuning_done
     tuning_out->xcd_remap = store->xcd_remap;
     tuning_out->lane_elems = store->lane_elems;
     tuning_out->resident_workgroups = store->resident_wgs;
+    tuning_out->run_time_w = store->generic_w;
     if (tuning_done_out) *tuning_done_out = store->tuner.active ? 0 : 1;
     return KV_OK;
 }

@@ -38,7 +38,8 @@ class _SgdParams(ctypes.Structure):
 
 class _Tuning(ctypes.Structure):
     _fields_ = [("unroll", ctypes.c_int), ("workgroups_per_cu", ctypes.c_int), ("nontemporal", ctypes.c_int),
-                ("xcd_remap", ctypes.c_int), ("lane_elems", ctypes.c_int), ("resident_workgroups", ctypes.c_int)]
+                ("xcd_remap", ctypes.c_int), ("lane_elems", ctypes.c_int), ("resident_workgroups", ctypes.c_int),
+                ("run_time_w", ctypes.c_int)]
 
 
 def library_path() -> str:
@@ -279,7 +280,7 @@ class KVStore:
                  reduce_order: int = KV_REDUCE_SEQUENTIAL, keep_sum: bool = False, descending: bool = False, lazy: bool = False,
                  stream: Optional[int] = None,
                  unroll: int = 0, workgroups_per_cu: int = -1, nontemporal: int = -1, xcd_remap: int = -1,
-                 lane_elems: int = 0, resident_workgroups: int = 0, autotune: bool = False):
+                 lane_elems: int = 0, resident_workgroups: int = 0, run_time_w: int = 0, autotune: bool = False):
         self._L = load_library()
         self._h = None
         self.key_numel = [int(x) for x in key_numel]
@@ -292,7 +293,7 @@ class KVStore:
         n = len(self.key_numel)
         arr = (ctypes.c_int64 * max(n, 1))(*self.key_numel)
         p = _SgdParams(lr, momentum, wd, rescale, reduce_order)
-        t = _Tuning(unroll, workgroups_per_cu, nontemporal, xcd_remap, lane_elems, resident_workgroups)
+        t = _Tuning(unroll, workgroups_per_cu, nontemporal, xcd_remap, lane_elems, resident_workgroups, run_time_w)
         h = ctypes.c_void_p()
         rc = self._L.kv_init(ctypes.byref(h), n, arr, self.grad_dtype, self.W, int(bucket_bytes), ctypes.byref(p),
                              (KV_FLAG_KEEP_SUM if keep_sum else 0) | (KV_FLAG_DESCENDING if descending else 0) |

@@ -152,6 +152,23 @@ def test_run_time_rank_counts_at_every_lane_width(dtype, lane_elems, W):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("W", [2, 4, 8, 16, 32])
+@pytest.mark.parametrize("order", [orc.SEQUENTIAL, orc.PAIRWISE])
+def test_run_time_w_kernel_at_the_rank_counts_that_have_a_kernel_of_their_own(dtype, W, order):
+    """tuning.run_time_w sends W = 2 ... 32 through the kernel that takes W at run time: same bits as the oracle,
+    hence as the kernels built for those W."""
+    pair = Pair(RAGGED, W, dtype, 16 << 10, lr=0.1, momentum=0.9, wd=1e-4, order=order, run_time_w=1)
+    try:
+        assert pair.gpu.get_tuning()[0]["run_time_w"] == 1
+        pair.set_weights([_rng(1, k).standard_normal(n, dtype=F) for k, n in enumerate(RAGGED)])
+        for t in range(2):
+            pair.step(_grads(RAGGED, W, dtype, 100 + t))
+            pair.compare(f"run-time-W kernel W={W} {dtype} order={order} step {t}")
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
 @pytest.mark.parametrize("lane_elems,unroll", [(4, 1), (4, 2), (4, 4), (2, 1), (2, 2), (1, 1), (1, 2), (1, 4)])
 @pytest.mark.parametrize("tuning", [dict(), dict(workgroups_per_cu=1), dict(xcd_remap=0), dict(nontemporal=0), dict(nontemporal=1), dict(nontemporal=5), dict(nontemporal=9), dict(nontemporal=13),
                                     dict(workgroups_per_cu=2, xcd_remap=1), dict(workgroups_per_cu=3, xcd_remap=0), dict(xcd_remap=1),
@@ -772,7 +789,7 @@ def test_init_rejects_bad_arguments():
 
 def test_tuning_values_round_trip_and_bad_ones_are_refused():
     import paper_1802_06949_amd as kv
-    want = dict(unroll=2, workgroups_per_cu=3, nontemporal=5, xcd_remap=128, lane_elems=2, resident_workgroups=6)
+    want = dict(unroll=2, workgroups_per_cu=3, nontemporal=5, xcd_remap=128, lane_elems=2, resident_workgroups=6, run_time_w=1)
     st = kv.KVStore([1000, 5000], 4, "f32", 1 << 12, lr=0.1, **want)
     try:
         got, settled = st.get_tuning()
@@ -787,7 +804,8 @@ def test_tuning_values_round_trip_and_bad_ones_are_refused():
     finally:
         st.close()
     for bad in (dict(workgroups_per_cu=65), dict(xcd_remap=(1 << 20) + 1), dict(resident_workgroups=2), dict(resident_workgroups=9),
-                dict(resident_workgroups=-1), dict(nontemporal=2), dict(lane_elems=3), dict(lane_elems=2, unroll=4)):
+                dict(resident_workgroups=-1), dict(nontemporal=2), dict(lane_elems=3), dict(lane_elems=2, unroll=4), dict(run_time_w=2),
+                dict(run_time_w=-1)):
         with pytest.raises(kv.KVError) as e:
             kv.KVStore([1000], 4, "f32", 1 << 12, lr=0.1, **bad)
         assert e.value.status == -1, bad
