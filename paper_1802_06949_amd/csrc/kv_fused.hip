@@ -242,6 +242,47 @@ __device__ __forceinline__ void fold_batch(Fold& f, const uint64_t KV_CONST* gp,
     }
 }
 
+// The last W - r0 < RS ranks (RS = 8 or 4) as pieces of 4, 2 and 1 ranks: the loads of all pieces are issued
+// before the first fold, behind three uniform branches.  (One guarded load per rank, each behind its own
+// branch, came out as one memory round trip per rank.)
+template <bool F16, int N, int RS, bool NT, typename Fold>
+__device__ __forceinline__ void fold_tail(Fold& f, const uint64_t KV_CONST* gp, int r0, int W, int64_t boff) {
+    using V = typename Grad<F16, N>::vec;
+    const int rem = W - r0;
+    const bool h4 = RS > 4 && (rem & 4) != 0, h2 = (rem & 2) != 0, h1 = (rem & 1) != 0;
+    const int r4 = r0, r2 = r4 + (h4 ? 4 : 0), r1 = r2 + (h2 ? 2 : 0);
+    V g4[4], g2[2], g1;
+    if (h4) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) g4[j] = load_grad<NT>((const V KV_GLOBAL*)(gp[r4 + j] + (uint64_t)boff));
+    }
+    if (h2) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) g2[j] = load_grad<NT>((const V KV_GLOBAL*)(gp[r2 + j] + (uint64_t)boff));
+    }
+    if (h1) g1 = load_grad<NT>((const V KV_GLOBAL*)(gp[r1] + (uint64_t)boff));
+    loads_issued();
+    float t[N];
+    if (h4) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            widen<N>(g4[j], t);
+            f.push(t);
+        }
+    }
+    if (h2) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            widen<N>(g2[j], t);
+            f.push(t);
+        }
+    }
+    if (h1) {
+        widen<N>(g1, t);
+        f.push(t);
+    }
+}
+
 // Sum over ranks of the gradient vector (N values) that starts `boff` bytes into every rank's copy of the key.
 template <bool F16, int N, int WT, bool PAIRWISE, bool NT>
 __device__ __forceinline__ void reduce_vec(const uint64_t KV_CONST* gp, int W, int64_t boff, float (&s)[N]) {
@@ -264,8 +305,7 @@ __device__ __forceinline__ void reduce_vec(const uint64_t KV_CONST* gp, int W, i
         }
     } else {
         // W known only at run time: whole large batches (KV_RUNTIME_W_BYTES of gradients per lane in flight), at
-        // most one batch of half that size, then whole small batches, then one guarded small batch for what is
-        // left; always in rank order.
+        // most one batch of half that size, then whole small batches, then the tail; always in rank order.
         constexpr int RL0 = KV_RUNTIME_W_BYTES / (int)sizeof(V);
         constexpr int RL = RL0 < 8 ? 8 : RL0 > 32 ? 32 : RL0;
         constexpr int RM = RL / 2;                   // 16 .. 31 ranks of 4-byte vectors: one batch of 16 first
@@ -279,7 +319,7 @@ __device__ __forceinline__ void reduce_vec(const uint64_t KV_CONST* gp, int W, i
             }
         }
         for (; r0 + RS <= W; r0 += RS) fold_batch<F16, N, RS, false, NT>(f, gp, r0, W, boff);
-        if (r0 < W) fold_batch<F16, N, RS, true, NT>(f, gp, r0, W, boff);
+        if (r0 < W) fold_tail<F16, N, RS, NT>(f, gp, r0, W, boff);
     }
     f.finish(s);
 }
