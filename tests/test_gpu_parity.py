@@ -136,9 +136,9 @@ def test_ragged_keys_all_rank_counts(dtype, W, order):
 @pytest.mark.parametrize("lane_elems", [1, 2, 4])
 @pytest.mark.parametrize("W", [3, 5, 9, 12, 15, 17, 20, 31, 33, 36, 40, 47, 63, 64, 65, 72, 100])
 def test_run_time_rank_counts_at_every_lane_width(dtype, lane_elems, W):
-    """The kernel for a W known only at run time folds whole large batches, whole small batches and one guarded
-    batch; the batch sizes depend on the size of a lane's vector (2 to 16 bytes).  Every boundary of that scheme,
-    in both fold orders (pairwise on the odd counts)."""
+    """The kernel for a W known only at run time folds whole large batches, a half batch, whole small batches and
+    a tail of 4 + 2 + 1 ranks; the batch sizes depend on the size of a lane's vector (2 to 16 bytes).  Every
+    boundary of that scheme, in both fold orders (pairwise on the odd counts)."""
     order = orc.PAIRWISE if W % 2 else orc.SEQUENTIAL
     numel = [1, 255, 1024 + 7, 6000]
     pair = Pair(numel, W, dtype, 16 << 10, lr=0.1, momentum=0.9, wd=1e-4, order=order, lane_elems=lane_elems)
