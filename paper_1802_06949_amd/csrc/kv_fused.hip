@@ -151,6 +151,12 @@ template <int NV> struct FoldSeq {
         }
         ++count;
     }
+    // a rank that is known not to be the first one
+    __device__ __forceinline__ void push_next(const float (&v)[NV]) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) acc[i] = acc[i] + v[i];
+        ++count;
+    }
     __device__ __forceinline__ void finish(float (&o)[NV]) const {
 #pragma unroll
         for (int i = 0; i < NV; ++i) o[i] = acc[i];
@@ -188,6 +194,7 @@ template <int NV> struct FoldPair {
         }
         ++count;
     }
+    __device__ __forceinline__ void push_next(const float (&v)[NV]) { push(v); }
     __device__ __forceinline__ void finish(float (&o)[NV]) const {
         bool have = false;
 #pragma unroll
@@ -237,7 +244,8 @@ __device__ __forceinline__ void fold_batch(Fold& f, const uint64_t KV_CONST* gp,
         if (!GUARDED || r0 + j < W) {
             float t[N];
             widen<N>(g[j], t);
-            f.push(t);
+            if (j == 0) f.push(t);          // only a batch's first rank can be the first rank of all
+            else f.push_next(t);
         }
     }
 }
@@ -267,14 +275,16 @@ __device__ __forceinline__ void fold_tail(Fold& f, const uint64_t KV_CONST* gp, 
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             widen<N>(g4[j], t);
-            f.push(t);
+            if (j == 0) f.push(t);
+            else f.push_next(t);
         }
     }
     if (h2) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             widen<N>(g2[j], t);
-            f.push(t);
+            if (j == 0) f.push(t);
+            else f.push_next(t);
         }
     }
     if (h1) {
@@ -318,7 +328,12 @@ __device__ __forceinline__ void reduce_vec(const uint64_t KV_CONST* gp, int W, i
                 r0 += RM;
             }
         }
-        for (; r0 + RS <= W; r0 += RS) fold_batch<F16, N, RS, false, NT>(f, gp, r0, W, boff);
+        // fewer than 2 RS ranks are left here (RL is 2 RS or 4 RS, and RM = 2 RS in the latter case)
+        static_assert(RL == 2 * RS || (RL == 4 * RS && RM == 2 * RS), "batch tiers");
+        if (r0 + RS <= W) {
+            fold_batch<F16, N, RS, false, NT>(f, gp, r0, W, boff);
+            r0 += RS;
+        }
         if (r0 < W) fold_tail<F16, N, RS, NT>(f, gp, r0, W, boff);
     }
     f.finish(s);
