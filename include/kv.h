@@ -329,11 +329,15 @@ int kv_wait_event(kv_store* store, void* hip_event);
 /*
  * kv_wait(key >= 0): blocks the host until the key's last launched update and every pull of the key issued
  * after it are complete (the paper's WaitToRead on one tensor); KV_ERR_INCOMPLETE, without blocking, if the key is
- * pushed but its unit cannot be launched yet.  The store records one event per launch (and per such pull) in a
- * ring of 256 and waits for the key's event alone, so work queued later, or on other streams of the concurrent
- * schedule, does not delay the return.  It waits for the key's whole stream instead when the ring has moved on,
- * and after a launch that covered every unit of the store (one launch per iteration: no event is recorded on
- * that path, and the stream holds nothing else of the iteration).
+ * pushed but its unit cannot be launched yet.  Work on other streams of the concurrent schedule never delays the
+ * return; work queued later on the key's own stream delays it by a bounded amount: an event record per launch
+ * costs about as much host time as the launch itself, so a stream records a completion event only after every
+ * 8th launch (or pull) that may be waited for, or earlier once 64 MB of launch traffic have gone out since its
+ * last one, into a ring of 256, and the wait is for the first event of the key's stream at or after the key's
+ * launch: at most 7 later launches, or 64 MB of later traffic, whichever is less.  When the stream has recorded
+ * none since (or the ring has moved on), the wait is for the stream as it stands; so it is after a launch that
+ * covered every unit of the store (one launch per iteration: nothing is recorded on that path, and the stream
+ * holds nothing else of the iteration).
  * kv_wait(-1): barrier (the paper's Kvstore.barrier): drains the stream, then
  * returns KV_ERR_INCOMPLETE if an iteration is only partly pushed or launched.
  */

@@ -52,6 +52,10 @@ struct kv_store;
 int kv_push_list_repeat(struct kv_store* store, int nkeys, const int* keys /* host */,
                         const void* const* dev_grads /* host */, int reps);
 
+/* Completion events recorded so far for kv_wait(key) (see there: one per 8 launches of a stream, or per 64 MB of
+ * launch traffic): what a test reads to see that a run of small launches shares events and a large one gets its own. */
+int kv_completion_events(const struct kv_store* store, int64_t* count_out /* host */);
+
 #ifdef __cplusplus
 }
 #endif

@@ -46,7 +46,9 @@ namespace {
 constexpr int NSLOT = 8;    // cached device pointer tables
 constexpr int NSTAGE = 8;   // pinned staging chunks in flight
 constexpr int LOG_CAP = 4096;
-constexpr int DONE_RING = 256; // completion events kept for kv_wait(key)
+constexpr int DONE_RING = 256;              // completion events kept for kv_wait(key)
+constexpr int DONE_EVERY = 8;               // launches of one stream between two completion events, at most
+constexpr int64_t DONE_BYTES = 64LL << 20;  // ... and bytes of launch traffic between two of them, at most
 
 // One cut of the key set into tiles (depends on the elements per tile): the device table, the first
 // tile of every unit and of every segment (tiles of segment g: [seg_tile_begin[g], seg_tile_begin[g + 1])).
@@ -72,6 +74,11 @@ struct Tuner {
     hipEvent_t e0 = nullptr, e1 = nullptr;
 };
 constexpr int TUNE_REPS = 2;
+
+struct DoneMark {
+    int stream = -1;
+    int64_t ordinal = 0;
+};
 
 struct Deferred {
     int key;
@@ -122,12 +129,19 @@ struct kv_store {
     bool stage_busy[NSTAGE] = {};
     int stage_next = 0;
 
-    // Completion events, one per launch (or copy) that kv_wait(key) may have to wait for, in a ring; a key
-    // remembers the serial number of the last one that covers it (-1: none, wait for the key's stream).
+    // What kv_wait(key) waits for.  Every launch (or copy) that a key may have to be waited for through gets a
+    // mark: the stream it went to (0: the store's, 1 + i: lane i) and its ordinal among that stream's marks.
+    // An event record per launch costs about as much host time as the launch itself, so a stream records one
+    // only every DONE_EVERY marks, or earlier once DONE_BYTES of traffic have been launched since the last one
+    // (a large key gets its own; a run of small ones shares one).  kv_wait(key) waits for the earliest event of
+    // the key's stream at or after the key's mark that the ring still holds, else for the stream.
     hipEvent_t done_ev[DONE_RING] = {};
-    int64_t done_serial[DONE_RING];
-    int64_t next_serial = 0;
-    std::vector<int64_t> key_serial;              // per key
+    int done_stream[DONE_RING];
+    int64_t done_ordinal[DONE_RING];
+    int64_t done_recorded = 0;                    // events recorded so far; the next one goes to slot % DONE_RING
+    std::vector<int64_t> marks_issued, marks_at_event, bytes_since_event;   // per stream index
+    std::vector<DoneMark> key_mark;               // per key; stream -1: none, wait for the key's stream
+    int64_t last_launch_bytes = 0;                // traffic of the launch launch_tiles issued last
     std::vector<uint8_t> want;                    // kv_pull_list: segments asked for (sized at kv_init)
 
     std::vector<std::vector<Deferred>> deferred;  // per unit
@@ -276,14 +290,26 @@ int table_for(kv_store* st, int s0, int s1, hipStream_t stream, const void* cons
 
 bool capturing(kv_store* st);
 
-// Records the next completion event of the ring on `stream` and returns its serial number (never inside a
-// capture: a captured event record is no event the host could wait for).
-int record_done(kv_store* st, hipStream_t stream, int64_t* serial_out) {
-    const int64_t serial = st->next_serial++;
-    const int slot = (int)(serial % DONE_RING);
-    KV_HIP(st, hipEventRecord(st->done_ev[slot], stream));
-    st->done_serial[slot] = serial;
-    *serial_out = serial;
+// Gives the work just issued on `stream` (`bytes` of traffic) the stream's next mark, and records a completion
+// event when the stream is due one (never called inside a capture: a captured event record is no event the
+// host could wait for).
+int mark_done(kv_store* st, hipStream_t stream, int64_t bytes, DoneMark* out) {
+    int idx = 0;
+    for (size_t i = 0; i < st->lanes.size(); ++i)
+        if (st->lanes[i] == stream) idx = 1 + (int)i;
+    const int64_t ordinal = ++st->marks_issued[(size_t)idx];
+    st->bytes_since_event[(size_t)idx] += bytes;
+    if (ordinal - st->marks_at_event[(size_t)idx] >= DONE_EVERY || st->bytes_since_event[(size_t)idx] >= DONE_BYTES) {
+        const int slot = (int)(st->done_recorded % DONE_RING);
+        KV_HIP(st, hipEventRecord(st->done_ev[slot], stream));
+        st->done_stream[slot] = idx;
+        st->done_ordinal[slot] = ordinal;
+        ++st->done_recorded;
+        st->marks_at_event[(size_t)idx] = ordinal;
+        st->bytes_since_event[(size_t)idx] = 0;
+    }
+    out->stream = idx;
+    out->ordinal = ordinal;
     return KV_OK;
 }
 
@@ -293,12 +319,10 @@ int issue_copy_out(kv_store* st, int key, void* dst, int what, hipStream_t strea
     if (n == 0) return KV_OK;
     KV_HIP(st, hipMemcpyAsync(dst, base + st->plan.key_arena_off[key], (size_t)n * sizeof(float), hipMemcpyDefault,
                               stream));
-    // kv_wait(key) covers the key's pulls: if the key is waited for through an event, the copy gets a later one
-    if (st->key_serial[(size_t)key] >= 0 && !st->capture_launch && !capturing(st)) {
-        int64_t serial = -1;
-        int rc = record_done(st, stream, &serial);
+    // kv_wait(key) covers the key's pulls: if the key is waited for through a mark, the copy gets a later one
+    if (st->key_mark[(size_t)key].stream >= 0 && !st->capture_launch && !capturing(st)) {
+        int rc = mark_done(st, stream, 2 * n * (int64_t)sizeof(float), &st->key_mark[(size_t)key]);
         if (rc != KV_OK) return rc;
-        st->key_serial[(size_t)key] = serial;
     }
     return KV_OK;
 }
@@ -386,6 +410,7 @@ int launch_tiles(kv_store* st, int s0, int s1, hipStream_t stream, int log_a, in
     }
     if (grid > 0x7FFFFFF0LL) grid = 0x7FFFFFF0LL;       // multiple of 8; the tile loop strides
     KV_HIP(st, kv_launch_fused(sel, a, (unsigned)grid, stream));
+    st->last_launch_bytes = total * ((int64_t)st->W * st->plan.itemsize + 4 * (int64_t)sizeof(float));
     if ((int)st->log.size() < LOG_CAP) st->log.emplace_back(log_a, log_b);
     else st->log[(size_t)(st->launches_total % LOG_CAP)] = std::make_pair(log_a, log_b);
     ++st->launches_total;
@@ -465,16 +490,16 @@ int launch_run(kv_store* st, int first, int n) {
         KV_HIP(st, hipEventRecord(st->tuner.e1, st->stream));
         st->tuner.pending = true;
     }
-    // kv_wait(key) waits for this launch alone through an event.  A launch that covers the whole key set gets
+    // kv_wait(key) can wait for this launch through its mark.  A launch that covers the whole key set gets
     // none (one event record per step is measurable on the headline path, and after such a launch waiting for
     // the stream is the same thing); neither does a captured launch.
-    int64_t serial = -1;
+    DoneMark mk;
     if (n < (int)st->plan.units.size() && !st->capture_launch) {
-        rc = record_done(st, st->stream, &serial);
+        rc = mark_done(st, st->stream, st->last_launch_bytes, &mk);
         if (rc != KV_OK) return rc;
     }
     for (int u = first; u < first + n; ++u)
-        for (int k : st->plan.units[u].keys) st->key_serial[(size_t)k] = serial;
+        for (int k : st->plan.units[u].keys) st->key_mark[(size_t)k] = mk;
     for (int u = first; u < first + n; ++u) {
         for (const Deferred& d : st->deferred[u]) {
             rc = issue_copy_out(st, d.key, d.dst, d.what, st->stream);
@@ -534,17 +559,15 @@ int launch_key(kv_store* st, int key) {
     if (rc != KV_OK) return rc;
     rc = launch_tiles(st, sgm, sgm + 1, stream, key, 0);
     if (rc != KV_OK) return rc;
-    st->key_serial[(size_t)key] = -1;
+    st->key_mark[(size_t)key] = DoneMark{};
     if (st->schedule == KV_SCHED_FUNNEL) {
         // the issuing thread does the aggregation itself: nothing else is started before it is done
         KV_HIP(st, hipStreamSynchronize(stream));
         return KV_OK;
     }
     if (!st->capture_launch) {
-        int64_t serial = -1;
-        rc = record_done(st, stream, &serial);
+        rc = mark_done(st, stream, st->last_launch_bytes, &st->key_mark[(size_t)key]);
         if (rc != KV_OK) return rc;
-        st->key_serial[(size_t)key] = serial;
     }
     if (st->outstanding > 0 && ++st->since_barrier >= st->outstanding) {
         return barrier_all(st);
@@ -933,7 +956,10 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
         st->deferred.resize(st->plan.units.size());
         for (size_t u = 0; u < st->plan.units.size(); ++u)      // room for a pull of w, m and s per key queued on a unit
             st->deferred[u].reserve(3 * st->plan.units[u].keys.size());
-        st->key_serial.assign((size_t)num_keys, -1);
+        st->key_mark.assign((size_t)num_keys, DoneMark{});
+        st->marks_issued.assign(1 + KV_MAX_STREAMS, 0);
+        st->marks_at_event.assign(1 + KV_MAX_STREAMS, 0);
+        st->bytes_since_event.assign(1 + KV_MAX_STREAMS, 0);
         st->want.assign(st->plan.seg_key.size(), 0);
         st->log.reserve(LOG_CAP);          // the launch path never allocates
     } catch (const std::bad_alloc&) {
@@ -980,7 +1006,8 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     for (int i = 0; i < NSTAGE; ++i) KV_INIT_HIP(hipEventCreateWithFlags(&st->stage_ev[i], hipEventDisableTiming));
     for (int i = 0; i < DONE_RING; ++i) {
         KV_INIT_HIP(hipEventCreateWithFlags(&st->done_ev[i], hipEventDisableTiming));
-        st->done_serial[i] = -1;
+        st->done_stream[i] = -1;
+        st->done_ordinal[i] = 0;
     }
     KV_INIT_HIP(hipEventCreateWithFlags(&st->fork_ev, hipEventDisableTiming));
     KV_INIT_HIP(hipEventCreateWithFlags(&st->join_ev, hipEventDisableTiming));
@@ -1215,15 +1242,17 @@ int kv_pull_list(kv_store* store, int nkeys, const int* keys, void* const* dev_o
                                        store->d_gather, store->stream));
         a = b;
     }
-    // kv_wait(key) covers the key's pulls: keys waited for through an event get the event after the gather
-    int64_t serial = -1;
+    // kv_wait(key) covers the key's pulls: keys waited for through a mark get the mark of the gather
+    DoneMark mk;
     for (int i = 0; i < nkeys; ++i) {
-        if (store->key_serial[(size_t)keys[i]] < 0) continue;
-        if (serial < 0) {
-            int rc = record_done(store, store->stream, &serial);
+        if (store->key_mark[(size_t)keys[i]].stream < 0) continue;
+        if (mk.stream < 0) {
+            int64_t bytes = 0;
+            for (int j = 0; j < nkeys; ++j) bytes += 2 * store->plan.numel[(size_t)keys[j]] * (int64_t)sizeof(float);
+            int rc = mark_done(store, store->stream, bytes, &mk);
             if (rc != KV_OK) return rc;
         }
-        store->key_serial[(size_t)keys[i]] = serial;
+        store->key_mark[(size_t)keys[i]] = mk;
     }
     return KV_OK;
 }
@@ -1249,13 +1278,19 @@ int kv_wait(kv_store* store, int key) {
             set_err(store->err, "kv_wait: key %d is pushed but its unit waits for other keys or lower units", key);
             return KV_ERR_INCOMPLETE;
         }
-        // the event of the key's last launch (or of a pull issued after it) if the ring still holds it
-        const int64_t serial = store->key_serial[(size_t)key];
-        if (serial >= 0 && store->done_serial[serial % DONE_RING] == serial) {
-            KV_HIP(store, hipEventSynchronize(store->done_ev[serial % DONE_RING]));
-            return KV_OK;
+        // the earliest event held that the key's stream recorded at or after the key's last launch (or a pull
+        // issued after it); without one (the stream has issued fewer than DONE_EVERY marks since) the stream
+        const DoneMark mk = store->key_mark[(size_t)key];
+        int best = -1;
+        if (mk.stream >= 0) {
+            const int held = store->done_recorded < DONE_RING ? (int)store->done_recorded : DONE_RING;
+            for (int i = 0; i < held; ++i)
+                if (store->done_stream[i] == mk.stream && store->done_ordinal[i] >= mk.ordinal &&
+                    (best < 0 || store->done_ordinal[i] < store->done_ordinal[best]))
+                    best = i;
         }
-        KV_HIP(store, hipStreamSynchronize(key_stream(store, key)));
+        if (best >= 0) KV_HIP(store, hipEventSynchronize(store->done_ev[best]));
+        else KV_HIP(store, hipStreamSynchronize(key_stream(store, key)));
         return KV_OK;
     }
     if (key != -1) {
@@ -1378,6 +1413,12 @@ int kv_wide_launches(const kv_store* store, int64_t* count_out) {
     return KV_OK;
 }
 
+int kv_completion_events(const kv_store* store, int64_t* count_out) {
+    if (!store || !count_out) return KV_ERR_ARG;
+    *count_out = store->done_recorded;
+    return KV_OK;
+}
+
 int kv_release_captures(kv_store* store) {
     if (!store) return KV_ERR_ARG;
     for (int i = 0; i < NSLOT; ++i) store->pinned[i] = false;
@@ -1438,6 +1479,8 @@ int kv_set_schedule(kv_store* store, int schedule, int n_streams, int outstandin
     }
     store->since_barrier = 0;
     store->schedule = schedule;
+    // everything is complete, and a key's stream may be another one from here on
+    for (DoneMark& mk : store->key_mark) mk = DoneMark{};
     return KV_OK;
 }
 

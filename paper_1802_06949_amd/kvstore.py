@@ -111,6 +111,7 @@ def load_library() -> ctypes.CDLL:
     sig("kv_evict_caches", c_int, c_vp, c_sz, c_int, c_vp)
     sig("kv_null_launch", c_int, c_int, c_vp)
     sig("kv_push_list_repeat", c_int, c_vp, c_int, P(c_int), P(c_vp), c_int)
+    sig("kv_completion_events", c_int, c_vp, P(c_i64))
     sig("kv_last_error", ctypes.c_char_p, c_vp)
     _lib = L
     return L
@@ -229,11 +230,24 @@ class Chain:
 _TORCH_DTYPE = {KV_F32: "torch.float32", KV_F16: "torch.float16"}
 
 
+_torch_dtypes = None
+
+
 def check_tensor(t, numel: int, dtype_code: int, what: str) -> None:
     """Host-side bounds check before a pointer crosses the C ABI: the kernels read or write exactly `numel`
-    elements of the given dtype at data_ptr(), so anything else would be an out-of-bounds device access."""
+    elements of the given dtype at data_ptr(), so anything else would be an out-of-bounds device access.
+    The passing case is four attribute reads (this runs once per gradient copy of every push)."""
+    global _torch_dtypes
     if numel == 0:
         return                                       # nothing of an empty key is ever read or written
+    if _torch_dtypes is None:
+        import torch
+        _torch_dtypes = {KV_F32: torch.float32, KV_F16: torch.float16}
+    try:
+        if t.is_cuda and t.dtype is _torch_dtypes[dtype_code] and t.numel() == numel and t.is_contiguous():
+            return
+    except AttributeError:
+        pass
     if not getattr(t, "is_cuda", False):
         raise ValueError(f"{what}: expected a tensor in GPU memory")
     if str(t.dtype) != _TORCH_DTYPE[dtype_code]:
@@ -370,6 +384,12 @@ class KVStore:
         """kv_push_list_repeat (kv_diag.h): the same list push `reps` times from native code, for timing
         launch-bound stores without the interpreter between the launches."""
         self._check(self._L.kv_push_list_repeat(self._h, pl.n, pl.keys, pl.ptrs, int(reps)))
+
+    def completion_events(self) -> int:
+        """kv_completion_events (kv_diag.h): completion events recorded so far for wait(key)."""
+        n = ctypes.c_int64()
+        self._check(self._L.kv_completion_events(self._h, ctypes.byref(n)))
+        return int(n.value)
 
     def push_list_noalloc(self, pl: PushList) -> None:
         """kv_push_list_noalloc: the list push that allocates and uploads nothing (static device pointer table)."""

@@ -147,6 +147,44 @@ def test_wait_for_one_key_covers_its_launch_and_its_pulls(schedule):
         pair.close()
 
 
+def test_small_launches_share_completion_events_and_a_large_one_gets_its_own():
+    """A stream records a completion event after every 8th launch that may be waited for, or once 64 MB of launch
+    traffic have gone out since its last one; kv_wait(key) waits for the first event of the key's stream at or after
+    the key's launch, else for the stream.  Two streams: key 0 (4 ranks of 3M floats and the state: 96 MB) and twenty
+    small keys on the first, twenty small keys on the second."""
+    import torch
+    numel = [3 << 20] + [776 + 12 * k for k in range(40)]
+    W = 4
+    pair = Pair(numel, W, "f32", 64 << 10, lr=0.5, momentum=0.9, wd=0.0, schedule=(CONCURRENT, 2, 0))
+    try:
+        pair.set_weights([_rng(70, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
+        arena = [type("P", (), {"data_ptr": lambda self, p=pair.gpu.weights_ptr(k): p})() for k in range(len(numel))]
+        outs = [torch.zeros(n, device="cuda") for n in numel]
+        side = torch.cuda.Stream()                     # a stream that is ordered after nothing of the store's
+        recorded = pair.gpu.completion_events()
+        for t in range(2):
+            g = _grads(numel, W, "f32", 71 + t)
+            dev = pair.upload(g)
+            torch.cuda.synchronize()
+            for k in range(len(numel)):
+                pair.gpu.push(k, dev[k])
+            # first stream: key 0 by its bytes, then the 8th and 16th of the twenty after it; second stream: its
+            # 8th and 16th (the counts carry over from one step to the next: 20 more marks, 2 or 3 more events)
+            now = pair.gpu.completion_events()
+            assert 5 <= now - recorded <= 6, (t, now - recorded)
+            recorded = now
+            pair.cpu.step(g)
+            for k in reversed(range(len(numel))):
+                pair.gpu.wait(k)
+                pair.kv.copy_bytes(outs[k], arena[k], numel[k] * 4, stream=side.cuda_stream)
+                side.synchronize()
+                assert np.array_equal(outs[k].cpu().numpy().view(np.uint32), pair.cpu.w[k].view(np.uint32)), f"step {t} key {k}"
+            assert pair.gpu.completion_events() == recorded     # waiting records nothing
+            pair.gpu.wait()
+    finally:
+        pair.close()
+
+
 def test_lazy_store_merges_single_pushes_into_one_launch():
     """The paper's Dependency Chaining loop: all pushes first, then the pulls.  With
     KV_FLAG_LAZY_LAUNCH the single pushes pile up and the whole iteration is one launch."""
