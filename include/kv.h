@@ -274,9 +274,9 @@ int kv_push_list_noalloc(kv_store* store, int nkeys, const int* keys /* host */,
 /* The launch tuning in force (the defaults resolved, or what KV_FLAG_AUTOTUNE has chosen so far);
  * *tuning_done_out (may be NULL) is 0 while a store that tunes itself is still trying shapes. */
 int kv_get_tuning(const kv_store* store, kv_tuning* tuning_out /* host */, int* tuning_done_out /* host */);
-/* Gradient buffers off the cache-line grid: a store whose default shape is one element per lane (8 and more fp32
- * ranks, 32 and more fp16 ranks; not when kv_tuning fixes lane_elems or unroll, nor while KV_FLAG_AUTOTUNE is trying
- * shapes) launches with four elements per lane instead when more than half of a launch's gradient elements lie in
+/* Gradient buffers off the cache-line grid: a store whose default shape is one element per lane, or two with 8 and
+ * more ranks (that is: 8 and more fp32 ranks; 8, 16, or 24 and more fp16 ranks; not when kv_tuning fixes lane_elems
+ * or unroll, nor while KV_FLAG_AUTOTUNE is trying shapes) launches with four elements per lane instead when more than half of a launch's gradient elements lie in
  * keys with a gradient pointer that is not a multiple of 128 bytes (views into a flat buffer) while all of them are
  * multiples of one 4-element vector.  Same bits, fewer cache lines fetched twice.  *count_out = launches so far that
  * took that shape (kv_get_tuning keeps reporting the default one). */

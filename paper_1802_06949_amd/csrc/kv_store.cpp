@@ -329,11 +329,12 @@ int issue_copy_out(kv_store* st, int key, void* dst, int what, hipStream_t strea
 
 // One fused kernel launch over the tiles of segments [s0, s1).
 //
-// Shape of the launch: the store's (one element per lane for 8 and more fp32 ranks, ...), except when most of the
-// launch's gradient bytes sit in buffers that do not start on a 128-byte line -- views into a flat buffer, say.
-// Every wavefront's 256-byte piece of such a stream straddles a line that its neighbour fetches again (8 fp32
-// ranks: +7 %, 32 ranks: +21 %, 32 fp16 ranks: +31 %); with 4 elements per lane a workgroup covers 4 KB per stream
-// and the shared lines are a quarter as many (+3 %, +4 %, +8 %).  The store keeps a second tile table for that.
+// Shape of the launch: the store's (one or two elements per lane for 8 and more ranks, ...), except when most of
+// the launch's gradient bytes sit in buffers that do not start on a 128-byte line -- views into a flat buffer, say.
+// With one element per lane every wavefront's 256-byte piece of such a stream straddles a line that its neighbour
+// fetches again (8 fp32 ranks: +7 %, 32 ranks: +21 %, 32 fp16 ranks: +31 %; two elements per lane, 16 ranks: +8 %
+// fp32, +11 % fp16); with 4 elements per lane a workgroup covers 4 KB per stream and the shared lines are a quarter
+// as many (+3 %, +4 %, +8 %; +4 %, +4 %).  The store keeps a second tile table for that.
 int launch_tiles(kv_store* st, int s0, int s1, hipStream_t stream, int log_a, int log_b) {
     if (st->ts->seg_tile_begin[(size_t)s1] <= st->ts->seg_tile_begin[(size_t)s0]) return KV_OK;
     const void* const* table = nullptr;
@@ -857,27 +858,31 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     // their own (ResNet-50-shaped key set).
     const int64_t state_bytes = 2 * st->plan.arena_numel * (int64_t)sizeof(float);
     const bool resident = state_bytes <= (256LL << 20);
-    // the kernel for any W: measured on the ResNet-50-shaped key set at W = 3, 12, 24, 40, 64
-    int lane = grad_dtype == KV_F16 ? (W < 24 ? 4 : W < 36 ? 2 : 1) : (W < 8 ? 4 : W < 24 ? 2 : 1);
+    // the kernel for any W: measured on the ResNet-50-shaped key set at W = 1, 3, 5, 6, 7, 12, 20, 24, 40, 64
+    int lane = grad_dtype == KV_F16 ? (W < 24 ? 4 : W < 36 ? 2 : 1) : (W < 5 ? 4 : W < 18 ? 2 : 1);
     {
         static const int w_built[5] = {2, 4, 8, 16, 32};
-        static const int lane_f32[5] = {4, 2, 1, 1, 1};
-        static const int lane_f16[5] = {4, 4, 2, 4, 1};
+        static const int lane_f32[5] = {4, 2, 1, 2, 1};
+        static const int lane_f16[5] = {4, 4, 2, 2, 1};
         for (int i = 0; i < 5; ++i)
             if (W == w_built[i]) lane = grad_dtype == KV_F16 ? lane_f16[i] : lane_f32[i];
+        // state that is streamed: one element per lane from 16 ranks on, for either dtype
+        if (!resident && W == 16) lane = 1;
     }
-    // With 16 or 32 fp32 ranks even one element per lane keeps more bytes in flight per compute
-    // unit than the memory system likes; fewer resident workgroups are worth another 2-3 %.  When
-    // the state does not fit the memory-side cache a cap pays for every rank count (3-8 %; measured
-    // on the VGG-16-shaped key set); with resident state and few ranks it costs.
+    // From 16 ranks on even a narrow lane keeps more bytes in flight per compute unit than the memory
+    // system likes; fewer resident workgroups are worth another 1-2 %.  When the state does not fit the
+    // memory-side cache a cap pays from 2 ranks on (3-8 %; measured on the VGG-16-shaped key set); with
+    // resident state and few ranks it costs.
     st->resident_wgs = 0;
     if (grad_dtype == KV_F32) {
-        if (W == 16) st->resident_wgs = resident ? 5 : 4;
+        if (W == 16) st->resident_wgs = 4;
         if (W == 32) st->resident_wgs = 4;
+        if (W > 32) st->resident_wgs = 5;
         if (!resident && W == 2) st->resident_wgs = 5;
         if (!resident && (W == 4 || W == 8)) st->resident_wgs = 6;
-    } else if (!resident && W == 16) {
-        st->resident_wgs = 5;
+    } else {
+        if (resident && W == 16) st->resident_wgs = 5;
+        if (!resident && W == 8) st->resident_wgs = 6;
     }
     st->unroll = 1;
     st->lane_elems = lane;
@@ -938,9 +943,10 @@ int kv_init(kv_store** out, int num_keys, const int64_t* key_numel, int grad_dty
     const bool autotune = (flags & KV_FLAG_AUTOTUNE) != 0;
     const int lane_idx = st->lane_elems == 1 ? 0 : st->lane_elems == 2 ? 1 : 2;
     st->ts = &st->sets[lane_idx];
-    // a store that runs one element per lane by default (not by the caller's choice) also gets the table for four:
+    // a store that runs one element per lane by default (not by the caller's choice), or two with 8 and more ranks,
+    // also gets the table for four:
     // launch_tiles switches to it for gradient buffers that are off the 128-byte line grid
-    st->wide_ready = st->lane_elems == 1 && st->unroll == 1 && !(tuning && (tuning->lane_elems != 0 || tuning->unroll != 0));
+    st->wide_ready = (st->lane_elems == 1 || (st->lane_elems == 2 && W >= 8)) && st->unroll == 1 && !(tuning && (tuning->lane_elems != 0 || tuning->unroll != 0));
     const bool build_set[3] = {lane_idx == 0 || autotune, lane_idx == 1 || autotune, lane_idx == 2 || autotune || st->wide_ready};
     try {
         for (int i = 0; i < 3; ++i) {

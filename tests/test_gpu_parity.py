@@ -257,17 +257,17 @@ def test_one_misaligned_buffer_among_aligned_ones(W, dtype, lane):
         pair.close()
 
 
-@pytest.mark.parametrize("W,dtype", [(8, "f32"), (16, "f32"), (32, "f16"), (40, "f16"), (33, "f32")])
+@pytest.mark.parametrize("W,dtype", [(8, "f32"), (16, "f32"), (16, "f16"), (32, "f16"), (40, "f16"), (33, "f32")])
 @pytest.mark.parametrize("mode", ["list", "each"])
 def test_views_off_the_line_grid_take_the_wide_shape_and_the_same_bits(W, dtype, mode):
     """Gradient views that start 32 bytes off a 128-byte line (but on a 4-element vector): a store whose default
-    is one element per lane launches them with four.  Step 0: all keys off the grid (wide launches); step 1: only a
+    is one element per lane (or two, with 8 and more ranks) launches them with four.  Step 0: all keys off the grid (wide launches); step 1: only a
     small key off the grid (default shape); step 2: one buffer 4 bytes off (no 4-element vectors: default shape)."""
     numel = [4096, 300, 40000 + 12, 1024, 70000]
     isz = 4 if dtype == "f32" else 2
     pair = Pair(numel, W, dtype, 64 << 10, lr=0.1, momentum=0.9, wd=1e-4)
     try:
-        assert pair.gpu.get_tuning()[0]["lane_elems"] == 1
+        assert pair.gpu.get_tuning()[0]["lane_elems"] == (2 if W == 16 else 1)
         pair.set_weights([_rng(6, k).standard_normal(n, dtype=F) for k, n in enumerate(numel)])
         wide_before = pair.gpu.wide_launches()
         for t in range(3):
